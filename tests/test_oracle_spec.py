@@ -1,0 +1,178 @@
+"""Pins for the decode loop: losslessness, counters, LDLP (Alg. 1, Eq. 1-3, Table 2)."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2412_18910_amd import synth
+from paper_2412_18910_amd.config import TINY
+
+from .helpers import make_oracle
+
+PROMPT, NGEN = 64, 128   # the tiny lossless configuration: 64 prompt ids, 128 generated tokens
+
+
+@pytest.fixture(scope="module")
+def ar_reference():
+    m, w = make_oracle(TINY, 0)
+    ids = synth.token_ids(PROMPT, TINY.vocab, 100)
+    m.prefill(ids)
+    first = m.pending
+    return ids, w, first, m.ar_greedy(NGEN)
+
+
+def _run_spec(w, ids, n_gen, k_of_step, script=None, formal=None):
+    """Loop of Alg. 1 on the oracle.  script[r] = number of leading draft tokens forced to
+    equal the formal sequence (the next one is forced to mismatch); None = natural draft."""
+    m, _ = make_oracle(TINY, 0, weights=w)
+    m.prefill(ids)
+    out, stats = [], dict(N_draft=0, N_target=0, N_waste=0, steps=[])
+    r = 0
+    while len(out) < n_gen:
+        k = k_of_step(r, m)
+        ov = None
+        if script is not None and k > 0:
+            a = min(int(script[r]), k)
+            ov = -np.ones(k, np.int32)
+            pos = len(out)
+            ov[:a] = formal[pos:pos + a]
+            if a < k:
+                ov[a] = (int(formal[pos + a]) + 1) % TINY.vocab
+        kk, na, toks = m.step(k_force=k, override_ids=ov)
+        assert kk == k and len(toks) == na + 1
+        out.extend(int(t) for t in toks)
+        stats["N_draft"] += k
+        stats["N_target"] += 1
+        stats["N_waste"] += k - na
+        stats["steps"].append((k, na))
+        r += 1
+    return np.array(out[:n_gen], np.int32), stats, len(out)
+
+
+def test_greedy_speculative_equals_autoregressive_natural_draft(ar_reference):
+    ids, w, _, ar = ar_reference
+    out, st, _ = _run_spec(w, ids, NGEN, lambda r, m: m.ldlp()[0])
+    assert np.array_equal(out, ar)
+    ks = {k for k, _ in st["steps"]}
+    assert len(ks) > 2, "LDLP of the synthetic weights should spread over several lengths"
+
+
+def test_greedy_speculative_equals_autoregressive_scripted_acceptance(ar_reference):
+    ids, w, _, ar = ar_reference
+    formal = np.concatenate([ar, ar[:32]])  # padding so slices past the end stay defined
+    script = synth.truncated_geometric(4 * NGEN, 3.5, TINY.k_max, 7)
+    out, st, total = _run_spec(w, ids, NGEN, lambda r, m: m.ldlp()[0], script, formal)
+    assert np.array_equal(out, ar)
+    # forced prefix => accepted length is at least the script (the forced mismatch stops it
+    # unless k was shorter than the script)
+    for (k, na), a in zip(st["steps"], script):
+        assert na == min(int(a), k)
+    assert total == st["N_draft"] - st["N_waste"] + st["N_target"]
+
+
+@pytest.mark.parametrize("sched", ["zeros", "kmax", "cycle"])
+def test_greedy_lossless_under_adversarial_lengths(ar_reference, sched):
+    ids, w, _, ar = ar_reference
+    f = {"zeros": lambda r, m: 0, "kmax": lambda r, m: TINY.k_max, "cycle": lambda r, m: r % (TINY.k_max + 1)}[sched]
+    out, st, total = _run_spec(w, ids, 48, f)
+    assert np.array_equal(out, ar[:48])
+    if sched == "zeros":  # k = 0 is a plain autoregressive step: one token per target forward
+        assert st["N_target"] == 48 and st["N_draft"] == 0
+
+
+def test_counter_identities_fixed_and_oracle_lengths(ar_reference):
+    ids, w, _, ar = ar_reference
+    formal = np.concatenate([ar, ar[:32]])
+    script = synth.truncated_geometric(4 * NGEN, 3.5, TINY.k_max, 8)
+    # fixed length k: N_draft = k * N_target (Table 2, EAGLE rows)
+    for k in (2, 5):
+        out, st, total = _run_spec(w, ids, 64, lambda r, m: k, script, formal)
+        assert st["N_draft"] == k * st["N_target"]
+        assert st["N_waste"] == sum(kk - na for kk, na in st["steps"])
+        assert total == sum(na + 1 for _, na in st["steps"])
+    # draft-length oracle: k = the scripted acceptance length => nothing wasted (Sec. 2.4)
+    out, st, total = _run_spec(w, ids, 64, lambda r, m: int(script[r]), script, formal)
+    assert st["N_waste"] == 0
+    assert np.array_equal(out, ar[:64])
+
+
+def test_table2_rows_obey_the_counter_definitions():
+    path = os.path.join(os.path.dirname(__file__), "golden", "table2_counts.txt")
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    assert len(rows) == 7
+    for name, tau, toks, nd, nt, nw in rows:
+        nd, nt, nw = int(nd), int(nt), int(nw)
+        if name.isdigit():
+            assert nd == int(name) * nt          # fixed length: k drafts per target forward
+        if name == "dyn_oracle":
+            assert nw == 0
+        # tokens per target forward = accepted drafts + 1 bonus; tau is its per-sample average,
+        # so the pooled ratio only has to be close
+        assert abs((nd - nw + nt) / nt - float(tau)) < 0.12
+
+
+def test_ldlp_closed_forms():
+    cfg = TINY
+    w = synth.make_weights(cfg, 0)
+    ids = synth.token_ids(8, cfg.vocab, 5)
+    # zero input layer => z = b_in, y = sum w_out silu(b_in) + b_out
+    w0 = dict(w)
+    w0["ldlp_w_in"] = torch.zeros_like(w["ldlp_w_in"])
+    w0["ldlp_b_in"] = torch.full_like(w["ldlp_b_in"], 0.75)
+    m, _ = make_oracle(cfg, 0, weights=w0)
+    m.prefill(ids)
+    k, y = m.ldlp()
+    s = 0.75 / (1 + np.exp(-0.75))
+    want = float(w["ldlp_w_out"].double().sum() * s + w["ldlp_b_out"].double()[0])
+    assert abs(y - want) < 1e-4 * max(1, abs(want))
+    assert k == min(cfg.k_max, max(0, int(np.rint(want))))
+
+
+@pytest.mark.parametrize("mode,n_res", [(0, 0), (1, 0), (0, 2)])
+def test_ldlp_matches_library_expression(mode, n_res):
+    cfg = TINY.with_(ldlp_in_mode=mode, ldlp_n_res=n_res)
+    m, w = make_oracle(cfg, 9)
+    ids = synth.token_ids(10, cfg.vocab, 6)
+    m.prefill(ids)
+    k, y = m.ldlp()
+    f = torch.from_numpy(m.feature((10 - 1) % (cfg.k_max + 1))).double()   # last prompt row (prefill runs in k_max+1 row chunks)
+    e = w["tok_emb"].double()[int(ids[-1])]               # embedding of the SAME token, not the bonus
+    u = torch.cat([e, f]) if mode == 0 else f
+    z = torch.nn.functional.linear(u, w["ldlp_w_in"].double(), w["ldlp_b_in"].double())
+    for r in range(n_res):
+        z = z + torch.nn.functional.silu(torch.nn.functional.linear(z, w["ldlp_w_res"][r].double(), w["ldlp_b_res"][r].double()))
+    want = float(torch.nn.functional.silu(z) @ w["ldlp_w_out"].double() + w["ldlp_b_out"].double()[0])
+    assert abs(y - want) < 1e-4
+    assert k == int(min(cfg.k_max, max(0, np.rint(want))))
+
+
+def test_ldlp_uses_feature_of_last_accepted_row(ar_reference):
+    """After a step with k° accepted, Eq. 3 reads row k° of the verify block (Sec. 3.2)."""
+    ids, w, _, ar = ar_reference
+    m, _ = make_oracle(TINY, 0, weights=w)
+    m.prefill(ids)
+    ov = np.array([ar[0], ar[1], (int(ar[2]) + 1) % TINY.vocab, -1], np.int32)
+    k, na, toks = m.step(k_force=4, override_ids=ov)
+    assert na == 2 and list(toks) == [ar[0], ar[1], ar[2]]
+    f_row2 = m.feature(2)
+    _, y = m.ldlp()
+    e = w["tok_emb"].double()[int(ar[1])]                 # last validated token, not the bonus ar[2]
+    u = torch.cat([e, torch.from_numpy(f_row2).double()])
+    z = torch.nn.functional.linear(u, w["ldlp_w_in"].double(), w["ldlp_b_in"].double())
+    want = float(torch.nn.functional.silu(z) @ w["ldlp_w_out"].double() + w["ldlp_b_out"].double()[0])
+    assert abs(y - want) < 1e-4
+
+
+def test_state_errors():
+    from oracle.binding import OracleError
+    m, _ = make_oracle(TINY, 0)
+    with pytest.raises(OracleError):
+        m.ldlp()                      # nothing prefetched yet
+    m.prefill(synth.token_ids(4, TINY.vocab, 1))
+    with pytest.raises(OracleError):
+        m.verify(n_rows=1)            # no draft to verify
+    with pytest.raises(OracleError):
+        m.draft(TINY.k_max + 1)
+    with pytest.raises(OracleError):
+        m.verify([TINY.vocab])        # id out of range
