@@ -1,0 +1,174 @@
+/*
+ * libadaeagle -- C ABI of the AdaEAGLE speculative decode step on one AMD MI355X
+ * (gfx950).  The step follows arxiv 2412.18910: a Lightweight Draft Length
+ * Predictor chooses the draft length k (Eq. 3), an EAGLE-style draft head chains k
+ * cached forwards (Eq. 2, Sec. 2.2), the target verifies the (k+1)-row block in one
+ * forward against its KV cache (Eq. 1), the acceptance rule runs (Sec. 2.1; greedy
+ * "validated prefix" of Sec. 3.1) and the KV cache is rolled back; Algorithm 1 is the
+ * loop over ae_step.
+ *
+ * Conventions
+ *  - All functions return AE_OK (0) or a negative ae_status; nothing throws or aborts.
+ *    ae_last_error() gives a human-readable reason (NULL ctx: reason of the last
+ *    failed ae_init on this thread).
+ *  - One ae_ctx = one sequence on one HIP stream.  A ctx is not thread-safe; calls
+ *    on one ctx must not overlap.  Distinct ctxs are independent.
+ *  - "host" / "device" below says where a pointer must live.  Weights and the stream
+ *    are owned by the caller and must outlive the ctx; with AE_BF16 the ctx keeps its
+ *    own re-tiled copy of every matrix (made in ae_init, 2 bytes per parameter), so
+ *    the caller's copies are only read during ae_init and by the embedding lookup.
+ *    Everything else (KV cache, activations, logits, scratch) is owned by the ctx.
+ *  - Output arrays are caller-owned host memory, filled before the call returns
+ *    (such calls synchronise the stream).
+ *  - Token positions in the paper are 1-based; cache slots and rotary positions
+ *    here are 0-based: token t_{s+1} lives in slot s.  kv_len = n = number of tokens
+ *    whose K/V are cached; the pending token (last bonus) is t_{n+1}, not yet cached.
+ *  - Matrices are row-major [out_features, in_features] in cfg.dtype (bf16 bit
+ *    patterns or float); every 1-D vector (norm gains, biases, LDLP output row)
+ *    is float.
+ *  - Shapes: head_dim in {64, 128}; 1 <= k_max <= 15; with AE_BF16 every matrix
+ *    needs out_features % 16 == 0 and in_features % 32 == 0 (else AE_EUNSUPPORTED).
+ */
+#ifndef ADAEAGLE_H
+#define ADAEAGLE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ae_ctx ae_ctx;
+
+typedef enum {
+  AE_OK = 0,
+  AE_EINVAL = -1,       /* argument out of range (k, rows, ids, capacity, NULL) */
+  AE_ESTATE = -2,       /* call not allowed in the current state of the sequence */
+  AE_ENOMEM = -3,       /* device or host allocation failed */
+  AE_EHIP = -4,         /* a HIP runtime call failed; see ae_last_error */
+  AE_EUNSUPPORTED = -5  /* shape or option outside what the kernels implement */
+} ae_status;
+
+typedef enum { AE_BF16 = 0, AE_FP32 = 1 } ae_dtype;
+
+typedef struct {
+  int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  float rope_base, rms_eps;
+  int32_t dtype;         /* ae_dtype of matrices and of the KV cache */
+  int32_t k_max;         /* upper clamp of Eq. 3; verify blocks have <= k_max+1 rows */
+  int32_t n_ctx_max;     /* KV capacity in tokens (context + generated + k_max + 1) */
+  int32_t ldlp_in_mode;  /* 0: LDLP input [e ; f] (Sec. 3.2)   1: f only */
+  int32_t ldlp_hidden;   /* width h of the LDLP hidden layers (<= 1024) */
+  int32_t ldlp_n_res;    /* residual h->h blocks between input and output layer */
+  float temperature;     /* 0: greedy (Sec. 3.1); > 0: rejection sampling (Sec. 2.1) */
+} ae_config;
+
+/* One pre-norm Llama-style decoder layer (device pointers). */
+typedef struct {
+  const float *attn_norm;                       /* [d] */
+  const void *wq, *wk, *wv, *wo;                /* [H*hd,d] [Hkv*hd,d] [Hkv*hd,d] [d,H*hd] */
+  const float *ffn_norm;                        /* [d] */
+  const void *w_gate, *w_up, *w_down;           /* [f,d] [f,d] [d,f] */
+} ae_layer_w;
+
+/* All device pointers.  The draft head reuses tok_emb and lm_head (Sec. 2.2). */
+typedef struct {
+  const void *tok_emb;        /* [V, d] */
+  const float *final_norm;    /* [d] */
+  const void *lm_head;        /* [V, d] */
+  const ae_layer_w *layers;   /* HOST array of n_layers entries holding device pointers */
+  ae_layer_w draft_layer;     /* the one EAGLE-style layer */
+  const void *draft_fc_w;     /* [d, 2d]; input columns = [target feature ; token embedding] */
+  const float *draft_fc_b;    /* [d] or NULL */
+  const void *ldlp_w_in;      /* [h, 2d] (in_mode 0) or [h, d] */
+  const float *ldlp_b_in;     /* [h] */
+  const void *ldlp_w_res;     /* [n_res, h, h] or NULL */
+  const float *ldlp_b_res;    /* [n_res, h] or NULL */
+  const float *ldlp_w_out;    /* [h] */
+  const float *ldlp_b_out;    /* [1] */
+} ae_weights;
+
+/* Validates cfg, re-tiles bf16 matrices, allocates the KV cache and work buffers on the
+ * current device, and binds the ctx to `hip_stream` (a hipStream_t; NULL = the default
+ * stream).  *out is NULL on failure. */
+int ae_init(const ae_config *cfg, const ae_weights *w, void *hip_stream, ae_ctx **out);
+void ae_free(ae_ctx *ctx);
+const char *ae_last_error(const ae_ctx *ctx);
+
+/* First iteration of Algorithm 1 (k = 0, T = prompt): runs the n prompt tokens (host
+ * ids) through the target in blocks of <= 16 rows and through the draft head for every
+ * slot whose next token is known; leaves kv_len = n and pending = first new token. */
+int ae_prefill(ae_ctx *ctx, const int32_t *prompt_ids, int n);
+
+/* Test / benchmark set-up: install K and V rows (host float [n][n_kv_heads*head_dim],
+ * converted to the cache dtype) for layer `layer` (n_layers = the draft layer) at
+ * slots 0..n-1 ...                                                                    */
+int ae_kv_import(ae_ctx *ctx, int layer, const float *k, const float *v, int n);
+/* ... and declare the state right after an accept: kv_len cached tokens, the token in
+ * the last slot, the pending bonus token and the feature row (host float [d]) of the
+ * last slot.  The draft cache is taken to be valid for slots 0..kv_len-2. */
+int ae_set_state(ae_ctx *ctx, int kv_len, int32_t last_tok, int32_t pending, const float *feat);
+
+/* Eq. 3: k = min(k_max, max(0, Round(MLP(e, f)))), round half to even.  e is the
+ * embedding of the last validated token, f its post-final-norm hidden state.
+ * y_out (nullable) receives the scalar before rounding. */
+int ae_ldlp(ae_ctx *ctx, int *k_out, float *y_out);
+
+/* Eq. 2: draft catch-up over the newly validated slots, then a chain of k-1 further
+ * one-row forwards; emits k tokens (argmax of the shared LM head, lowest id on ties;
+ * with temperature > 0 inverse-CDF samples driven by u_draft[i] in [0,1)).
+ * override_ids (host, nullable): entry i >= 0 replaces the i-th emitted token before it
+ * is chained.  draft_ids_out (host, nullable) receives the k tokens. */
+int ae_draft(ae_ctx *ctx, int k, const int32_t *override_ids, const double *u_draft,
+             int32_t *draft_ids_out);
+
+/* Eq. 1, forward part: target forward of an n_rows block at slots kv_len.. with causal
+ * attention over the cache; row i's logits judge block token i+1.  block_ids (host)
+ * NULL => the block is [pending, the k draft tokens] and n_rows must be k+1. */
+int ae_verify(ae_ctx *ctx, const int32_t *block_ids, int n_rows);
+
+/* Acceptance and rollback.  Greedy (temperature 0, u ignored): n_accepted = length of
+ * the longest draft prefix equal to the target argmax, bonus = target argmax of the
+ * next row.  temperature > 0: u (host) holds n_rows uniforms in [0,1): u[i], i < k,
+ * accepts draft token i+1 iff u[i] < min(1, p/p_hat); the first rejection resamples
+ * from norm(max(0, p - p_hat)) over the vocabulary, no rejection samples the bonus
+ * from the last row; both draws use u[k] by inverse CDF in token order, in float64.
+ * Afterwards kv_len += 1 + n_accepted (rows beyond are dead) and pending = bonus. */
+int ae_accept(ae_ctx *ctx, const double *u, int *n_accepted, int32_t *bonus);
+
+typedef struct {
+  /* inputs */
+  int32_t k_force;              /* >= 0: use this draft length instead of the LDLP's */
+  const int32_t *override_ids;  /* host, nullable: see ae_draft */
+  const double *u_draft;        /* host, [k_max]  (temperature > 0 only) */
+  const double *u_accept;       /* host, [k_max+1] (temperature > 0 only) */
+  /* outputs */
+  int32_t k;                    /* draft length used */
+  int32_t n_accepted;           /* k-circle of Eq. 1 */
+  int32_t n_tokens;             /* n_accepted + 1 */
+  int32_t tokens[16];           /* accepted draft tokens, then the bonus token */
+  float us_total;               /* wall time of the step, host clock */
+} ae_step_io;
+
+/* One iteration of Algorithm 1 in the order LDLP -> draft -> verify -> accept+rollback. */
+int ae_step(ae_ctx *ctx, ae_step_io *io);
+
+/* Introspection for parity tests (host outputs). */
+int ae_kv_len(const ae_ctx *ctx);
+int32_t ae_pending(const ae_ctx *ctx);
+int ae_get_logits(ae_ctx *ctx, int row, float *out_vocab);       /* last verify */
+int ae_get_feature(ae_ctx *ctx, int row, float *out_d);          /* last verify / prefill block */
+int ae_get_draft_logits(ae_ctx *ctx, int i, float *out_vocab);   /* behind draft token i */
+int ae_get_kv_row(ae_ctx *ctx, int layer, int which /*0=K 1=V*/, int slot, float *out_dkv);
+
+/* Phase timing: when enabled, ae_step brackets its phases with HIP events. */
+typedef struct { float us_ldlp, us_draft, us_verify, us_accept; } ae_phase_times;
+int ae_set_profiling(ae_ctx *ctx, int enabled);
+int ae_get_phase_times(ae_ctx *ctx, ae_phase_times *out);   /* of the last ae_step */
+
+const char *ae_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,508 @@
+// C ABI of libadaeagle: context set-up, the state machine of one sequence, and the
+// host-side sequencing of the kernels of one decode step (LDLP -> draft -> verify ->
+// accept + rollback, i.e. one iteration of Algorithm 1 of arxiv 2412.18910).
+#include <chrono>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "ae_internal.h"
+
+using namespace ae;
+
+namespace {
+
+thread_local std::string g_init_error;
+
+int fail(ae_ctx *c, int code, const std::string &msg) {
+  if (c) c->err = msg; else g_init_error = msg;
+  return code;
+}
+
+#define HIPCHK(c, call)                                                                          \
+  do {                                                                                           \
+    hipError_t e_ = (call);                                                                      \
+    if (e_ != hipSuccess)                                                                        \
+      return fail((c), e_ == hipErrorOutOfMemory ? AE_ENOMEM : AE_EHIP,                          \
+                  std::string(#call) + ": " + hipGetErrorString(e_));                            \
+  } while (0)
+
+template <typename T>
+int dev_alloc(ae_ctx *c, T **p, size_t count) {
+  void *q = nullptr;
+  hipError_t e = hipMalloc(&q, count * sizeof(T) + 256);
+  if (e != hipSuccess) return fail(c, AE_ENOMEM, std::string("hipMalloc: ") + hipGetErrorString(e));
+  c->owned.push_back(q);
+  *p = (T *)q;
+  return AE_OK;
+}
+
+size_t esize(const ae_config &c) { return c.dtype == AE_BF16 ? 2 : 4; }
+
+Mat make_mat(const void *p, int N, int K) {
+  Mat m;
+  m.rowmajor = p; m.N = N; m.K = K;
+  return m;
+}
+
+// Y[r][n] (+)= X[r][:] . W[n][:] + bias[n]
+void gemm(ae_ctx *c, const Mat &W, const float *X, int ldx, int rows, const float *bias, float *Y, int ldy,
+          int accumulate) {
+  launch_gemm_generic(W.rowmajor, c->cfg.dtype, W.N, W.K, X, ldx, rows, bias, Y, ldy, accumulate, c->stream);
+}
+
+void *kv_layer_ptr(ae_ctx *c, int li) { return (char *)c->kv + (size_t)li * c->kv_layer_stride; }
+
+// One pre-norm decoder layer over `rows` slots starting at pos0; x is updated in place.
+void run_layer(ae_ctx *c, int li, float *x, int rows, int pos0) {
+  const ae_config &g = c->cfg;
+  const LayerW &w = c->layers[li];
+  const int d = g.d_model, dq = g.n_heads * g.head_dim, dkv = g.n_kv_heads * g.head_dim, f = g.d_ffn;
+  hipStream_t s = c->stream;
+  launch_rmsnorm(x, w.attn_norm, rows, d, g.rms_eps, c->xn, s);
+  gemm(c, w.wq, c->xn, d, rows, nullptr, c->q, dq, 0);
+  gemm(c, w.wk, c->xn, d, rows, nullptr, c->kbuf, dkv, 0);
+  gemm(c, w.wv, c->xn, d, rows, nullptr, c->vbuf, dkv, 0);
+  launch_rope_append(c->q, c->kbuf, c->vbuf, rows, pos0, g, c->rope_tab, kv_layer_ptr(c, li), c->kv_v_offset, s);
+  launch_attention(c->q, rows, pos0, g, kv_layer_ptr(c, li), c->kv_v_offset, c->attn_part, c->att, s);
+  gemm(c, w.wo, c->att, dq, rows, nullptr, x, d, 1);
+  launch_rmsnorm(x, w.ffn_norm, rows, d, g.rms_eps, c->xn, s);
+  gemm(c, w.w_gate, c->xn, d, rows, nullptr, c->gate, f, 0);
+  gemm(c, w.w_up, c->xn, d, rows, nullptr, c->up, f, 0);
+  launch_silu_mul(c->gate, c->up, rows, f, c->hmid, s);
+  gemm(c, w.w_down, c->hmid, f, rows, nullptr, x, d, 1);
+}
+
+// Target forward of `rows` tokens (device ids) at slots pos0..; features -> F rows 0..rows-1;
+// logits (+ per-row argmax into st->argmax) for rows >= logit_from.
+void target_forward(ae_ctx *c, const int32_t *ids_dev, int rows, int pos0, int logit_from) {
+  const ae_config &g = c->cfg;
+  hipStream_t s = c->stream;
+  launch_embed(c->tok_emb, g.dtype, ids_dev, rows, g.d_model, c->x, s);
+  for (int l = 0; l < g.n_layers; ++l) run_layer(c, l, c->x, rows, pos0);
+  launch_rmsnorm(c->x, c->final_norm, rows, g.d_model, g.rms_eps, c->F, s);
+  if (logit_from < rows) {
+    const int nr = rows - logit_from;
+    gemm(c, c->lm_head, c->F + (size_t)logit_from * g.d_model, g.d_model, nr, nullptr, c->logits, g.vocab, 0);
+    launch_argmax(c->logits, nr, g.vocab, c->st->argmax, s);
+  }
+}
+
+// Draft head over `rows` slots from slot0: slot input = fc([feature ; emb(next token)]).
+// Leaves the head's outputs in x rows 0..rows-1.
+void draft_rows(ae_ctx *c, const float *feat, int feat_ld, const int32_t *next_ids_dev, int rows, int slot0) {
+  const ae_config &g = c->cfg;
+  hipStream_t s = c->stream;
+  launch_draft_cat(feat, feat_ld, c->tok_emb, g.dtype, next_ids_dev, rows, g.d_model, c->cat, s);
+  gemm(c, c->draft_fc, c->cat, 2 * g.d_model, rows, c->draft_fc_b, c->x, g.d_model, 0);
+  run_layer(c, g.n_layers, c->x, rows, slot0);
+}
+
+void enqueue_ldlp(ae_ctx *c, int slot, int f_row, bool relative_to_accept) {
+  const ae_config &g = c->cfg;
+  hipStream_t s = c->stream;
+  launch_ldlp_gather(c->tok_emb, g.dtype, c->hist, c->F, g.d_model, g.ldlp_in_mode, slot, f_row,
+                     relative_to_accept ? c->st : nullptr, c->ldlp_u, s);
+  const int in = g.ldlp_in_mode == 0 ? 2 * g.d_model : g.d_model;
+  launch_gemm_generic(c->ldlp_in.rowmajor, g.dtype, g.ldlp_hidden, in, c->ldlp_u, in, 1, c->ldlp_b_in, c->ldlp_z,
+                      g.ldlp_hidden, 0, s);
+  launch_ldlp_tail(c->ldlp_z, c->ldlp_w_res, g.dtype, c->ldlp_b_res, c->ldlp_w_out, c->ldlp_b_out, g.ldlp_hidden,
+                   g.ldlp_n_res, g.k_max, c->st, s);
+}
+
+int read_state(ae_ctx *c) {
+  HIPCHK(c, hipMemcpyAsync(c->h_st, c->st, sizeof(DevState), hipMemcpyDeviceToHost, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipGetLastError());
+  return AE_OK;
+}
+
+__global__ void finish_prefill_kernel(DevState *st, int32_t *hist, int n) {
+  hist[n] = st->argmax[0];
+  st->bonus = st->argmax[0];
+  st->n_acc = 0;
+}
+
+bool ids_ok(const ae_ctx *c, const int32_t *ids, int n) {
+  for (int i = 0; i < n; ++i)
+    if (ids[i] < 0 || ids[i] >= c->cfg.vocab) return false;
+  return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *ae_version(void) { return "adaeagle-gfx950 0.1"; }
+
+const char *ae_last_error(const ae_ctx *ctx) { return ctx ? ctx->err.c_str() : g_init_error.c_str(); }
+
+int ae_init(const ae_config *cfg, const ae_weights *w, void *hip_stream, ae_ctx **out) {
+  if (out) *out = nullptr;
+  if (!cfg || !w || !out) return fail(nullptr, AE_EINVAL, "ae_init: NULL argument");
+  const ae_config &g = *cfg;
+  if (g.n_layers < 1 || g.d_model < 8 || g.n_heads < 1 || g.n_kv_heads < 1 || g.d_ffn < 8 || g.vocab < 1 ||
+      g.n_heads % g.n_kv_heads != 0 || g.k_max < 0 || g.n_ctx_max < 1 || g.ldlp_hidden < 1 || g.ldlp_n_res < 0 ||
+      (g.dtype != AE_BF16 && g.dtype != AE_FP32) || (g.ldlp_in_mode != 0 && g.ldlp_in_mode != 1) ||
+      !(g.temperature >= 0.f) || !(g.rms_eps >= 0.f) || !(g.rope_base > 0.f))
+    return fail(nullptr, AE_EINVAL, "ae_init: configuration field out of range");
+  if (g.head_dim != 64 && g.head_dim != 128) return fail(nullptr, AE_EUNSUPPORTED, "head_dim must be 64 or 128");
+  if (g.k_max + 1 > kMaxRows) return fail(nullptr, AE_EUNSUPPORTED, "k_max must be <= 15");
+  if (g.d_model % 8 || g.d_ffn % 8 || g.ldlp_hidden % 8 || g.ldlp_hidden > kMaxLdlpHidden)
+    return fail(nullptr, AE_EUNSUPPORTED, "d_model, d_ffn, ldlp_hidden must be multiples of 8 (ldlp_hidden <= 1024)");
+  if ((g.n_heads / g.n_kv_heads) * kMaxRows > 64)
+    return fail(nullptr, AE_EUNSUPPORTED, "n_heads / n_kv_heads must be <= 4");
+  if (g.n_ctx_max > kMaxSplits * kAttnChunk) return fail(nullptr, AE_EUNSUPPORTED, "n_ctx_max too large (<= 16384)");
+  if (g.temperature > 0.f) return fail(nullptr, AE_EUNSUPPORTED, "temperature > 0 is not implemented yet");
+  if (!w->tok_emb || !w->final_norm || !w->lm_head || !w->layers || !w->draft_fc_w || !w->ldlp_w_in ||
+      !w->ldlp_b_in || !w->ldlp_w_out || !w->ldlp_b_out || (g.ldlp_n_res > 0 && (!w->ldlp_w_res || !w->ldlp_b_res)))
+    return fail(nullptr, AE_EINVAL, "ae_init: NULL weight pointer");
+
+  ae_ctx *c = new (std::nothrow) ae_ctx();
+  if (!c) return fail(nullptr, AE_ENOMEM, "out of host memory");
+  c->cfg = g;
+  c->stream = (hipStream_t)hip_stream;
+  int rc = AE_OK;
+  auto bail = [&](int code) { g_init_error = c->err; ae_free(c); return code; };
+  if (hipGetDevice(&c->device) != hipSuccess) { c->err = "hipGetDevice failed (no GPU?)"; return bail(AE_EHIP); }
+
+  const int d = g.d_model, dq = g.n_heads * g.head_dim, dkv = g.n_kv_heads * g.head_dim, f = g.d_ffn, V = g.vocab;
+  auto conv_layer = [&](const ae_layer_w &s, LayerW &o) -> bool {
+    if (!s.attn_norm || !s.wq || !s.wk || !s.wv || !s.wo || !s.ffn_norm || !s.w_gate || !s.w_up || !s.w_down) return false;
+    o.attn_norm = s.attn_norm; o.ffn_norm = s.ffn_norm;
+    o.wq = make_mat(s.wq, dq, d); o.wk = make_mat(s.wk, dkv, d); o.wv = make_mat(s.wv, dkv, d);
+    o.wo = make_mat(s.wo, d, dq); o.w_gate = make_mat(s.w_gate, f, d); o.w_up = make_mat(s.w_up, f, d);
+    o.w_down = make_mat(s.w_down, d, f);
+    return true;
+  };
+  c->layers.resize(g.n_layers + 1);
+  for (int l = 0; l < g.n_layers; ++l)
+    if (!conv_layer(w->layers[l], c->layers[l])) { c->err = "ae_init: NULL layer weight"; return bail(AE_EINVAL); }
+  if (!conv_layer(w->draft_layer, c->layers[g.n_layers])) { c->err = "ae_init: NULL draft layer weight"; return bail(AE_EINVAL); }
+  c->tok_emb = w->tok_emb; c->final_norm = w->final_norm;
+  c->lm_head = make_mat(w->lm_head, V, d);
+  c->draft_fc = make_mat(w->draft_fc_w, d, 2 * d);
+  c->draft_fc_b = w->draft_fc_b;
+  c->ldlp_in = make_mat(w->ldlp_w_in, g.ldlp_hidden, g.ldlp_in_mode == 0 ? 2 * d : d);
+  c->ldlp_b_in = w->ldlp_b_in; c->ldlp_w_res = w->ldlp_w_res; c->ldlp_b_res = w->ldlp_b_res;
+  c->ldlp_w_out = w->ldlp_w_out; c->ldlp_b_out = w->ldlp_b_out;
+
+  // KV cache for n_layers target layers + the draft layer, zero-filled so that slots that
+  // were never written hold finite values
+  c->kv_layer_stride = kv_layer_bytes(g);
+  c->kv_v_offset = kv_v_offset_bytes(g);
+  const size_t kv_bytes = c->kv_layer_stride * (size_t)(g.n_layers + 1);
+  char *kvp = nullptr;
+  if ((rc = dev_alloc(c, &kvp, kv_bytes))) return bail(rc);
+  c->kv = kvp;
+  launch_fill_zero(c->kv, (kv_bytes + 15) / 16 * 16, c->stream);
+
+  const size_t R = kMaxRows;
+  const int dmax = dq > d ? dq : d;
+  if ((rc = dev_alloc(c, &c->rope_tab, (size_t)g.n_ctx_max * (g.head_dim / 2))) ||
+      (rc = dev_alloc(c, &c->x, R * d)) || (rc = dev_alloc(c, &c->xn, R * d)) ||
+      (rc = dev_alloc(c, &c->q, R * dq)) || (rc = dev_alloc(c, &c->kbuf, R * dkv)) ||
+      (rc = dev_alloc(c, &c->vbuf, R * dkv)) || (rc = dev_alloc(c, &c->att, R * dmax)) ||
+      (rc = dev_alloc(c, &c->gate, R * f)) || (rc = dev_alloc(c, &c->up, R * f)) ||
+      (rc = dev_alloc(c, &c->hmid, R * f)) || (rc = dev_alloc(c, &c->F, R * d)) ||
+      (rc = dev_alloc(c, &c->cat, R * 2 * d)) || (rc = dev_alloc(c, &c->logits, (size_t)(g.k_max + 1) * V)) ||
+      (rc = dev_alloc(c, &c->dlogits, (size_t)(g.k_max > 0 ? g.k_max : 1) * V)) ||
+      (rc = dev_alloc(c, &c->attn_part, attn_part_floats(g))) || (rc = dev_alloc(c, &c->ldlp_u, (size_t)2 * d)) ||
+      (rc = dev_alloc(c, &c->ldlp_z, (size_t)kMaxLdlpHidden)) ||
+      (rc = dev_alloc(c, &c->hist, (size_t)g.n_ctx_max + 2)) || (rc = dev_alloc(c, &c->st, 1)))
+    return bail(rc);
+  launch_rope_table(c->rope_tab, g.n_ctx_max, g.head_dim, g.rope_base, c->stream);
+  launch_fill_zero(c->st, (sizeof(DevState) + 15) / 16 * 16, c->stream);
+  launch_fill_zero(c->hist, ((size_t)(g.n_ctx_max + 2) * 4 + 15) / 16 * 16, c->stream);
+  if (hipHostMalloc((void **)&c->h_st, sizeof(DevState), hipHostMallocDefault) != hipSuccess ||
+      hipHostMalloc((void **)&c->h_ids, sizeof(DevState), hipHostMallocDefault) != hipSuccess) {
+    c->err = "hipHostMalloc failed";
+    return bail(AE_ENOMEM);
+  }
+  for (auto &e : c->ev)
+    if (hipEventCreate(&e) != hipSuccess) { c->err = "hipEventCreate failed"; return bail(AE_EHIP); }
+  c->h_hist.assign((size_t)g.n_ctx_max + 2, 0);
+  c->h_block.assign(kMaxRows, 0);
+  hipError_t e = hipStreamSynchronize(c->stream);
+  if (e == hipSuccess) e = hipGetLastError();
+  if (e != hipSuccess) { c->err = std::string("ae_init: ") + hipGetErrorString(e); return bail(AE_EHIP); }
+  *out = c;
+  return AE_OK;
+}
+
+void ae_free(ae_ctx *c) {
+  if (!c) return;
+  hipStreamSynchronize(c->stream);
+  for (void *p : c->owned) hipFree(p);
+  if (c->h_st) hipHostFree(c->h_st);
+  if (c->h_ids) hipHostFree(c->h_ids);
+  for (auto &e : c->ev)
+    if (e) hipEventDestroy(e);
+  delete c;
+}
+
+int ae_prefill(ae_ctx *c, const int32_t *ids, int n) {
+  if (!c) return AE_EINVAL;
+  const ae_config &g = c->cfg;
+  if (!ids || n < 1) return fail(c, AE_EINVAL, "ae_prefill: empty prompt");
+  if (n + g.k_max + 1 > g.n_ctx_max) return fail(c, AE_EINVAL, "ae_prefill: prompt does not fit n_ctx_max");
+  if (!ids_ok(c, ids, n)) return fail(c, AE_EINVAL, "ae_prefill: token id out of range");
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipMemcpy(c->hist, ids, sizeof(int32_t) * n, hipMemcpyHostToDevice));
+  memcpy(c->h_hist.data(), ids, sizeof(int32_t) * n);
+  c->kv_len = 0; c->dlen = 0; c->nF = 0;
+  c->have_pending = c->have_draft = c->have_verify = c->k_next_valid = false;
+  for (int p0 = 0; p0 < n; p0 += kMaxRows) {
+    const int rows = n - p0 < kMaxRows ? n - p0 : kMaxRows;
+    const bool last = p0 + rows == n;
+    target_forward(c, c->hist + p0, rows, p0, last ? rows - 1 : rows);
+    const int drows = last ? rows - 1 : rows;  // slots whose next token is in the prompt
+    if (drows > 0) draft_rows(c, c->F, g.d_model, c->hist + p0 + 1, drows, p0);
+    c->nF = rows;
+  }
+  finish_prefill_kernel<<<1, 1, 0, c->stream>>>(c->st, c->hist, n);
+  c->kv_len = n;
+  c->dlen = n - 1;
+  enqueue_ldlp(c, n - 1, c->nF - 1, false);
+  int rc = read_state(c);
+  if (rc) return rc;
+  c->pending = c->h_st->bonus;
+  c->h_hist[n] = c->pending;
+  c->k_next = c->h_st->k_next; c->y_next = c->h_st->y_next; c->k_next_valid = true;
+  c->have_pending = true;
+  c->cur_k = 0;
+  return AE_OK;
+}
+
+int ae_kv_import(ae_ctx *c, int layer, const float *k, const float *v, int n) {
+  if (!c) return AE_EINVAL;
+  const ae_config &g = c->cfg;
+  if (layer < 0 || layer > g.n_layers || n < 0 || n > g.n_ctx_max || !k || !v)
+    return fail(c, AE_EINVAL, "ae_kv_import: argument out of range");
+  if (n == 0) return AE_OK;
+  const size_t cnt = (size_t)n * g.n_kv_heads * g.head_dim;
+  float *tmp = nullptr;
+  HIPCHK(c, hipMalloc((void **)&tmp, 2 * cnt * sizeof(float)));
+  hipError_t e = hipMemcpy(tmp, k, cnt * sizeof(float), hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy(tmp + cnt, v, cnt * sizeof(float), hipMemcpyHostToDevice);
+  if (e == hipSuccess) {
+    launch_kv_import(kv_layer_ptr(c, layer), c->kv_v_offset, g, tmp, tmp + cnt, n, c->stream);
+    e = hipStreamSynchronize(c->stream);
+  }
+  hipFree(tmp);
+  if (e != hipSuccess) return fail(c, AE_EHIP, std::string("ae_kv_import: ") + hipGetErrorString(e));
+  return AE_OK;
+}
+
+int ae_set_state(ae_ctx *c, int kv_len, int32_t last_tok, int32_t pending, const float *feat) {
+  if (!c) return AE_EINVAL;
+  const ae_config &g = c->cfg;
+  if (kv_len < 1 || kv_len + g.k_max + 1 > g.n_ctx_max || !feat) return fail(c, AE_EINVAL, "ae_set_state: bad kv_len");
+  if (!ids_ok(c, &last_tok, 1) || !ids_ok(c, &pending, 1)) return fail(c, AE_EINVAL, "ae_set_state: id out of range");
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipMemcpy(c->F, feat, sizeof(float) * g.d_model, hipMemcpyHostToDevice));
+  const int32_t two[2] = {last_tok, pending};
+  HIPCHK(c, hipMemcpy(c->hist + kv_len - 1, two, sizeof(two), hipMemcpyHostToDevice));
+  c->h_hist[kv_len - 1] = last_tok; c->h_hist[kv_len] = pending;
+  c->kv_len = kv_len; c->dlen = kv_len - 1; c->nF = 1; c->pending = pending;
+  c->have_pending = true; c->have_draft = c->have_verify = false; c->k_next_valid = false; c->cur_k = 0;
+  return AE_OK;
+}
+
+int ae_ldlp(ae_ctx *c, int *k_out, float *y_out) {
+  if (!c) return AE_EINVAL;
+  if (!k_out) return fail(c, AE_EINVAL, "ae_ldlp: NULL output");
+  if (!c->have_pending || c->nF < 1) return fail(c, AE_ESTATE, "ae_ldlp: no validated token yet (prefill first)");
+  if (!c->k_next_valid) {
+    enqueue_ldlp(c, c->kv_len - 1, c->nF - 1, false);
+    int rc = read_state(c);
+    if (rc) return rc;
+    c->k_next = c->h_st->k_next; c->y_next = c->h_st->y_next; c->k_next_valid = true;
+  }
+  *k_out = c->k_next;
+  if (y_out) *y_out = c->y_next;
+  return AE_OK;
+}
+
+int ae_draft(ae_ctx *c, int k, const int32_t *override_ids, const double *u_draft, int32_t *out) {
+  if (!c) return AE_EINVAL;
+  const ae_config &g = c->cfg;
+  if (!c->have_pending) return fail(c, AE_ESTATE, "ae_draft: no pending token (prefill first)");
+  if (k < 0 || k > g.k_max) return fail(c, AE_EINVAL, "ae_draft: k outside [0, k_max]");
+  if (c->kv_len + k + 1 > g.n_ctx_max) return fail(c, AE_EINVAL, "ae_draft: KV capacity exceeded");
+  const int n = c->kv_len, catch_rows = n - c->dlen;
+  if (catch_rows < 1 || catch_rows > c->nF)
+    return fail(c, AE_ESTATE, "ae_draft: draft cache is stale (target advanced without the draft head)");
+  if (override_ids)
+    for (int i = 0; i < k; ++i)
+      if (override_ids[i] >= g.vocab) return fail(c, AE_EINVAL, "ae_draft: override id out of range");
+  (void)u_draft;
+  hipStream_t s = c->stream;
+  // upload the override table (-1 = keep the head's own token)
+  DevState *up = (DevState *)c->h_ids;
+  for (int i = 0; i < kMaxRows; ++i) up->override_ids[i] = (override_ids && i < k) ? override_ids[i] : -1;
+  HIPCHK(c, hipMemcpyAsync(c->st->override_ids, up->override_ids, sizeof(up->override_ids), hipMemcpyHostToDevice, s));
+  // catch-up over the slots validated by the last accept: true feature + following token
+  draft_rows(c, c->F + (size_t)(c->nF - catch_rows) * g.d_model, g.d_model, c->hist + c->dlen + 1, catch_rows, c->dlen);
+  c->dlen = n;
+  const float *fh = c->x + (size_t)(catch_rows - 1) * g.d_model;
+  for (int i = 0; i < k; ++i) {
+    if (i > 0) {  // chain: the head's previous output replaces the feature
+      draft_rows(c, fh, g.d_model, c->st->draft_ids + (i - 1), 1, n - 1 + i);
+      fh = c->x;
+    }
+    float *dl = c->dlogits + (size_t)i * g.vocab;
+    gemm(c, c->lm_head, fh, g.d_model, 1, nullptr, dl, g.vocab, 0);
+    launch_argmax(dl, 1, g.vocab, c->st->argmax, s);
+    launch_pick_draft(c->st, i, nullptr, s);
+  }
+  c->cur_k = k;
+  c->have_draft = true;
+  c->have_verify = false;
+  if (out && k > 0) {
+    int rc = read_state(c);
+    if (rc) return rc;
+    memcpy(out, c->h_st->draft_ids, sizeof(int32_t) * k);
+  }
+  return AE_OK;
+}
+
+int ae_verify(ae_ctx *c, const int32_t *block_ids, int rows) {
+  if (!c) return AE_EINVAL;
+  const ae_config &g = c->cfg;
+  if (!c->have_pending) return fail(c, AE_ESTATE, "ae_verify: no pending token (prefill first)");
+  if (rows < 1 || rows > g.k_max + 1) return fail(c, AE_EINVAL, "ae_verify: rows outside [1, k_max+1]");
+  if (c->kv_len + rows > g.n_ctx_max) return fail(c, AE_EINVAL, "ae_verify: KV capacity exceeded");
+  hipStream_t s = c->stream;
+  if (block_ids) {
+    if (!ids_ok(c, block_ids, rows)) return fail(c, AE_EINVAL, "ae_verify: token id out of range");
+    // the staging buffer may still feed an earlier asynchronous upload
+    HIPCHK(c, hipStreamSynchronize(s));
+    memcpy(c->h_ids, block_ids, sizeof(int32_t) * rows);
+    HIPCHK(c, hipMemcpyAsync(c->st->block, c->h_ids, sizeof(int32_t) * rows, hipMemcpyHostToDevice, s));
+  } else {
+    if (!c->have_draft || rows != c->cur_k + 1)
+      return fail(c, AE_ESTATE, "ae_verify: implicit block needs a draft of rows-1 tokens");
+    launch_build_block(c->st, c->hist, c->kv_len, c->cur_k, s);
+  }
+  target_forward(c, c->st->block, rows, c->kv_len, 0);
+  c->block_rows = rows;
+  c->have_verify = true;
+  return AE_OK;
+}
+
+int ae_accept(ae_ctx *c, const double *u, int *n_accepted, int32_t *bonus) {
+  if (!c) return AE_EINVAL;
+  if (!c->have_verify) return fail(c, AE_ESTATE, "ae_accept: nothing verified");
+  (void)u;
+  const int n = c->kv_len, rows = c->block_rows;
+  launch_accept_greedy(c->st, c->hist, n, rows, c->stream);
+  // Alg. 1 predicts the next draft length right after the verification
+  const bool spec = c->have_draft;
+  if (spec) enqueue_ldlp(c, n, 0, true);
+  int rc = read_state(c);
+  if (rc) return rc;
+  const int acc = c->h_st->n_acc;
+  for (int i = 0; i <= acc; ++i) c->h_hist[n + i] = c->h_st->block[i];
+  c->kv_len = n + 1 + acc;   // rollback: rows beyond the accepted prefix are dead
+  c->pending = c->h_st->bonus;
+  c->h_hist[c->kv_len] = c->pending;
+  memcpy(c->h_block.data(), c->h_st->block, sizeof(int32_t) * kMaxRows);
+  c->nF = acc + 1;
+  c->have_verify = c->have_draft = false;
+  c->cur_k = 0;
+  c->k_next_valid = spec;
+  if (spec) { c->k_next = c->h_st->k_next; c->y_next = c->h_st->y_next; }
+  if (n_accepted) *n_accepted = acc;
+  if (bonus) *bonus = c->pending;
+  return AE_OK;
+}
+
+int ae_step(ae_ctx *c, ae_step_io *io) {
+  if (!c) return AE_EINVAL;
+  if (!io) return fail(c, AE_EINVAL, "ae_step: NULL io");
+  const auto t0 = std::chrono::steady_clock::now();
+  const bool prof = c->profiling;
+  hipStream_t s = c->stream;
+  int rc, k = 0;
+  if (prof) hipEventRecord(c->ev[0], s);
+  if (io->k_force >= 0) {
+    k = io->k_force;
+  } else if ((rc = ae_ldlp(c, &k, nullptr))) {
+    return rc;
+  }
+  if (prof) hipEventRecord(c->ev[1], s);
+  if ((rc = ae_draft(c, k, io->override_ids, io->u_draft, nullptr))) return rc;
+  if (prof) hipEventRecord(c->ev[2], s);
+  if ((rc = ae_verify(c, nullptr, k + 1))) return rc;
+  if (prof) hipEventRecord(c->ev[3], s);
+  int acc = 0;
+  int32_t b = 0;
+  if ((rc = ae_accept(c, io->u_accept, &acc, &b))) return rc;
+  if (prof) {
+    hipEventRecord(c->ev[4], s);
+    hipEventSynchronize(c->ev[4]);
+    float ms[4] = {0, 0, 0, 0};
+    for (int i = 0; i < 4; ++i) hipEventElapsedTime(&ms[i], c->ev[i], c->ev[i + 1]);
+    c->last_times = {ms[0] * 1e3f, ms[1] * 1e3f, ms[2] * 1e3f, ms[3] * 1e3f};
+  }
+  io->k = k;
+  io->n_accepted = acc;
+  io->n_tokens = acc + 1;
+  for (int i = 0; i < acc; ++i) io->tokens[i] = c->h_block[1 + i];
+  io->tokens[acc] = b;
+  io->us_total = std::chrono::duration<float, std::micro>(std::chrono::steady_clock::now() - t0).count();
+  return AE_OK;
+}
+
+int ae_kv_len(const ae_ctx *c) { return c ? c->kv_len : AE_EINVAL; }
+int32_t ae_pending(const ae_ctx *c) { return c && c->have_pending ? c->pending : -1; }
+
+static int copy_out(ae_ctx *c, const float *src, size_t n, float *dst) {
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipMemcpy(dst, src, n * sizeof(float), hipMemcpyDeviceToHost));
+  return AE_OK;
+}
+
+int ae_get_logits(ae_ctx *c, int row, float *out) {
+  if (!c) return AE_EINVAL;
+  if (!out || row < 0 || row > c->cfg.k_max) return fail(c, AE_EINVAL, "ae_get_logits: bad row");
+  return copy_out(c, c->logits + (size_t)row * c->cfg.vocab, c->cfg.vocab, out);
+}
+
+int ae_get_feature(ae_ctx *c, int row, float *out) {
+  if (!c) return AE_EINVAL;
+  if (!out || row < 0 || row >= kMaxRows) return fail(c, AE_EINVAL, "ae_get_feature: bad row");
+  return copy_out(c, c->F + (size_t)row * c->cfg.d_model, c->cfg.d_model, out);
+}
+
+int ae_get_draft_logits(ae_ctx *c, int i, float *out) {
+  if (!c) return AE_EINVAL;
+  if (!out || i < 0 || i >= c->cfg.k_max) return fail(c, AE_EINVAL, "ae_get_draft_logits: bad index");
+  return copy_out(c, c->dlogits + (size_t)i * c->cfg.vocab, c->cfg.vocab, out);
+}
+
+int ae_get_kv_row(ae_ctx *c, int layer, int which, int slot, float *out) {
+  if (!c) return AE_EINVAL;
+  const ae_config &g = c->cfg;
+  if (!out || layer < 0 || layer > g.n_layers || (which != 0 && which != 1) || slot < 0 || slot >= g.n_ctx_max)
+    return fail(c, AE_EINVAL, "ae_get_kv_row: argument out of range");
+  launch_kv_export(kv_layer_ptr(c, layer), c->kv_v_offset, g, which, slot, c->attn_part, c->stream);
+  return copy_out(c, c->attn_part, (size_t)g.n_kv_heads * g.head_dim, out);
+}
+
+int ae_set_profiling(ae_ctx *c, int enabled) {
+  if (!c) return AE_EINVAL;
+  c->profiling = enabled != 0;
+  return AE_OK;
+}
+
+int ae_get_phase_times(ae_ctx *c, ae_phase_times *out) {
+  if (!c) return AE_EINVAL;
+  if (!out) return fail(c, AE_EINVAL, "ae_get_phase_times: NULL output");
+  *out = c->last_times;
+  return AE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,145 @@
+// Internal declarations of libadaeagle (gfx950).  Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "adaeagle.h"
+
+namespace ae {
+
+constexpr int kMaxRows = 16;       // rows of one verify / prefill block (one MFMA tile)
+constexpr int kAttnChunk = 256;    // keys per split-KV workgroup (fixed by absolute slot)
+constexpr int kMaxSplits = 64;     // n_ctx_max / kAttnChunk upper bound
+constexpr int kMaxLdlpHidden = 1024;
+
+// Device-resident step state.  The host mirrors kv_len (it learns it at every accept).
+struct DevState {
+  int32_t n_acc;            // result of the last accept
+  int32_t bonus;
+  int32_t k_next;           // Eq. 3 result for the next step
+  float y_next;             // LDLP scalar before rounding
+  int32_t draft_ids[kMaxRows];
+  int32_t override_ids[kMaxRows];
+  int32_t block[kMaxRows];  // ids of the verify block
+  int32_t argmax[kMaxRows]; // per-row argmax of the last LM-head call
+  double u_draft[kMaxRows];
+  double u_accept[kMaxRows];
+};
+
+// Weight matrix handle: row-major source plus (bf16 fast path) the re-tiled copy.
+struct Mat {
+  const void *rowmajor = nullptr;  // caller's [N,K]
+  void *tiled = nullptr;           // ctx-owned MFMA-tile layout, bf16 only
+  int N = 0, K = 0;
+};
+
+struct LayerW {
+  const float *attn_norm = nullptr, *ffn_norm = nullptr;
+  Mat wq, wk, wv, wo, w_gate, w_up, w_down;
+};
+
+}  // namespace ae
+
+struct ae_ctx {
+  ae_config cfg{};
+  hipStream_t stream = nullptr;
+  int device = 0;
+  bool fast = false;            // bf16 MFMA path (else generic kernels)
+  std::string err;
+
+  // weights
+  const void *tok_emb = nullptr;
+  const float *final_norm = nullptr;
+  ae::Mat lm_head, draft_fc, ldlp_in;
+  const float *draft_fc_b = nullptr, *ldlp_b_in = nullptr, *ldlp_b_res = nullptr;
+  const void *ldlp_w_res = nullptr;
+  const float *ldlp_w_out = nullptr, *ldlp_b_out = nullptr;
+  std::vector<ae::LayerW> layers;  // n_layers target layers + the draft layer last
+  std::vector<void *> owned;       // device allocations to free
+
+  // KV cache: per layer K in d-group-major layout, V row-major (see kernels_attn.hip)
+  void *kv = nullptr;
+  size_t kv_layer_stride = 0;      // bytes between layers
+  size_t kv_v_offset = 0;          // bytes from a layer's K to its V
+  float2 *rope_tab = nullptr;      // [n_ctx_max][head_dim/2] (cos, sin)
+
+  // activations (float, kMaxRows rows each)
+  float *x = nullptr, *xn = nullptr, *q = nullptr, *kbuf = nullptr, *vbuf = nullptr, *att = nullptr;
+  float *gate = nullptr, *up = nullptr, *hmid = nullptr;
+  float *F = nullptr;              // feature rows (post final norm)
+  float *fhat = nullptr;           // draft-head output rows
+  float *cat = nullptr;            // [rows][2d] draft fc input
+  float *logits = nullptr;         // [k_max+1][V]
+  float *dlogits = nullptr;        // [k_max][V]
+  float *attn_part = nullptr;      // split-KV partials
+  float *ldlp_u = nullptr, *ldlp_z = nullptr;
+  double *prob = nullptr;          // T>0 scratch [2][V]
+  int32_t *hist = nullptr;         // device token history by slot
+  ae::DevState *st = nullptr;      // device state
+  ae::DevState *h_st = nullptr;    // pinned host mirror used for read-back / uploads
+  int32_t *h_ids = nullptr;        // pinned staging for ids
+
+  // host-side state machine
+  int kv_len = 0, dlen = 0, nF = 0;
+  int cur_k = 0, block_rows = 0;
+  int32_t pending = 0;
+  bool have_pending = false, have_draft = false, have_verify = false, k_next_valid = false;
+  int k_next = 0;
+  float y_next = 0.f;
+  std::vector<int32_t> h_hist;     // host mirror of the token history
+  std::vector<int32_t> h_block;
+
+  // profiling
+  bool profiling = false;
+  hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
+  ae_phase_times last_times{};
+};
+
+namespace ae {
+
+// ---- generic kernels (kernels_generic.hip); all launches are asynchronous on `s` ----
+void launch_embed(const void *emb, int dtype, const int32_t *ids_dev, int rows, int d, float *out, hipStream_t s);
+void launch_rmsnorm(const float *x, const float *g, int rows, int d, float eps, float *out, hipStream_t s);
+// Y[r][n] (+)= sum_k X[r][k] W[n][k] + bias[n];  accumulate != 0 adds into Y (residual)
+void launch_gemm_generic(const void *W, int dtype, int N, int K, const float *X, int ldx, int rows,
+                         const float *bias, float *Y, int ldy, int accumulate, hipStream_t s);
+void launch_silu_mul(const float *gate, const float *up, int rows, int f, float *out, hipStream_t s);
+void launch_argmax(const float *logits, int rows, int V, int32_t *out_ids, hipStream_t s);
+void launch_draft_cat(const float *feat, int feat_ld, const void *emb, int dtype, const int32_t *next_ids,
+                      int rows, int d, float *cat, hipStream_t s);
+void launch_pick_draft(DevState *st, int i, int32_t *hist_slot, hipStream_t s);
+void launch_build_block(DevState *st, const int32_t *hist, int kv_len, int k, hipStream_t s);
+void launch_accept_greedy(DevState *st, int32_t *hist, int kv_len, int rows, hipStream_t s);
+void launch_ldlp_gather(const void *emb, int dtype, const int32_t *hist, const float *F, int d, int in_mode,
+                        int kv_len_minus1_or_neg, int f_row, const DevState *st, float *u, hipStream_t s);
+void launch_ldlp_tail(const float *z0, const void *w_res, int dtype, const float *b_res, const float *w_out,
+                      const float *b_out, int h, int n_res, int k_max, DevState *st, hipStream_t s);
+void launch_rope_table(float2 *tab, int n_pos, int head_dim, float base, hipStream_t s);
+void launch_fill_zero(void *p, size_t bytes, hipStream_t s);
+
+// ---- attention (kernels_attn.hip) ----
+size_t kv_layer_bytes(const ae_config &c);
+size_t kv_v_offset_bytes(const ae_config &c);
+void launch_rope_append(float *q, const float *k, const float *v, int rows, int pos0, const ae_config &c,
+                        const float2 *rope_tab, void *kv_layer, size_t v_off, hipStream_t s);
+void launch_attention(const float *q, int rows, int pos0, const ae_config &c, const void *kv_layer, size_t v_off,
+                      float *part, float *out, hipStream_t s);
+void launch_kv_import(void *kv_layer, size_t v_off, const ae_config &c, const float *k_dev, const float *v_dev, int n,
+                      hipStream_t s);
+void launch_kv_export(const void *kv_layer, size_t v_off, const ae_config &c, int which, int slot, float *out_dev,
+                      hipStream_t s);
+size_t attn_part_floats(const ae_config &c);
+
+// ---- T > 0 sampling (kernels_sample.hip) ----
+void launch_sample_draft(const float *logits, int V, float T, DevState *st, int i, double *prob, hipStream_t s);
+void launch_accept_sample(const float *tl, const float *dl, int V, int k, float T, DevState *st, int32_t *hist,
+                          int kv_len, double *prob, hipStream_t s);
+
+// ---- bf16 MFMA path (kernels_mfma.hip) ----
+void launch_retile(const void *rowmajor, int N, int K, void *tiled, hipStream_t s);
+
+}  // namespace ae

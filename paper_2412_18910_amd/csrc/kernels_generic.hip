@@ -1,0 +1,329 @@
+// Dtype-generic kernels of the decode step (gfx950, wave64).  They serve the fp32
+// configuration and every small op of the bf16 configuration; the bandwidth-critical
+// bf16 GEMMs have their own MFMA kernels in kernels_mfma.hip.
+#include "ae_internal.h"
+
+namespace ae {
+
+using bf16_t = uint16_t;
+
+__device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+template <typename T>
+__device__ __forceinline__ float ld1(const T *p);
+template <>
+__device__ __forceinline__ float ld1<float>(const float *p) { return *p; }
+template <>
+__device__ __forceinline__ float ld1<bf16_t>(const bf16_t *p) { return bf2f(*p); }
+
+// 8 consecutive weights -> float[8] with 128-bit loads
+__device__ __forceinline__ void ld8(const float *p, float *w) {
+  const float4 a = *reinterpret_cast<const float4 *>(p), b = *reinterpret_cast<const float4 *>(p + 4);
+  w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w; w[4] = b.x; w[5] = b.y; w[6] = b.z; w[7] = b.w;
+}
+__device__ __forceinline__ void ld8(const bf16_t *p, float *w) {
+  const uint4 a = *reinterpret_cast<const uint4 *>(p);
+  w[0] = __uint_as_float(a.x << 16); w[1] = __uint_as_float(a.x & 0xffff0000u);
+  w[2] = __uint_as_float(a.y << 16); w[3] = __uint_as_float(a.y & 0xffff0000u);
+  w[4] = __uint_as_float(a.z << 16); w[5] = __uint_as_float(a.z & 0xffff0000u);
+  w[6] = __uint_as_float(a.w << 16); w[7] = __uint_as_float(a.w & 0xffff0000u);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+__device__ __forceinline__ float silu_f(float x) { return x / (1.0f + expf(-x)); }
+
+// ------------------------------------------------------------------ embedding
+template <typename T>
+__global__ void embed_kernel(const T *emb, const int32_t *ids, int d, float *out) {
+  const int r = blockIdx.x;
+  const T *src = emb + (size_t)ids[r] * d;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) out[(size_t)r * d + i] = ld1(src + i);
+}
+
+void launch_embed(const void *emb, int dtype, const int32_t *ids_dev, int rows, int d, float *out, hipStream_t s) {
+  if (dtype == AE_BF16)
+    embed_kernel<bf16_t><<<rows, 256, 0, s>>>((const bf16_t *)emb, ids_dev, d, out);
+  else
+    embed_kernel<float><<<rows, 256, 0, s>>>((const float *)emb, ids_dev, d, out);
+}
+
+// ------------------------------------------------------------------ RMSNorm
+// out = (x / sqrt(mean(x^2) + eps)) * g, one workgroup per row
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float *x, const float *g, int d, float eps, float *out) {
+  __shared__ float red[4];
+  const float *xr = x + (size_t)blockIdx.x * d;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) ss += xr[i] * xr[i];
+  ss = wave_sum(ss);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  const float tot = (red[0] + red[1]) + (red[2] + red[3]);
+  const float r = 1.0f / sqrtf(tot / (float)d + eps);
+  for (int i = threadIdx.x; i < d; i += 256) out[(size_t)blockIdx.x * d + i] = (xr[i] * r) * g[i];
+}
+
+void launch_rmsnorm(const float *x, const float *g, int rows, int d, float eps, float *out, hipStream_t s) {
+  rmsnorm_kernel<<<rows, 256, 0, s>>>(x, g, d, eps, out);
+}
+
+// ------------------------------------------------------------------ generic skinny GEMM
+// One wave per output column n, all rows at once; lanes stride over K in 8-element
+// pieces.  The per-output summation order does not depend on the number of rows.
+template <typename WT, int MT>
+__global__ __launch_bounds__(256) void gemm_generic_kernel(const WT *W, int N, int K, const float *X, int ldx, int rows,
+                                                           const float *bias, float *Y, int ldy, int accumulate) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int n = blockIdx.x * 4 + wave;
+  if (n >= N) return;
+  float acc[MT];
+#pragma unroll
+  for (int m = 0; m < MT; ++m) acc[m] = 0.f;
+  const WT *wrow = W + (size_t)n * K;
+  for (int k0 = lane * 8; k0 < K; k0 += 512) {
+    float w[8];
+    ld8(wrow + k0, w);
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+      if (m < rows) {
+        float xv[8];
+        ld8(X + (size_t)m * ldx + k0, xv);
+        float a = acc[m];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) a = fmaf(xv[j], w[j], a);
+        acc[m] = a;
+      }
+    }
+  }
+#pragma unroll
+  for (int m = 0; m < MT; ++m) {
+    if (m < rows) {
+      float v = wave_sum(acc[m]);
+      if (lane == 0) {
+        if (bias) v += bias[n];
+        float *y = Y + (size_t)m * ldy + n;
+        *y = accumulate ? *y + v : v;
+      }
+    }
+  }
+}
+
+template <typename WT>
+static void gemm_generic_dispatch(const WT *W, int N, int K, const float *X, int ldx, int rows, const float *bias,
+                                  float *Y, int ldy, int acc, hipStream_t s) {
+  const dim3 grid((N + 3) / 4);
+  if (rows <= 1)
+    gemm_generic_kernel<WT, 1><<<grid, 256, 0, s>>>(W, N, K, X, ldx, rows, bias, Y, ldy, acc);
+  else if (rows <= 4)
+    gemm_generic_kernel<WT, 4><<<grid, 256, 0, s>>>(W, N, K, X, ldx, rows, bias, Y, ldy, acc);
+  else
+    gemm_generic_kernel<WT, 16><<<grid, 256, 0, s>>>(W, N, K, X, ldx, rows, bias, Y, ldy, acc);
+}
+
+void launch_gemm_generic(const void *W, int dtype, int N, int K, const float *X, int ldx, int rows,
+                         const float *bias, float *Y, int ldy, int accumulate, hipStream_t s) {
+  if (dtype == AE_BF16)
+    gemm_generic_dispatch<bf16_t>((const bf16_t *)W, N, K, X, ldx, rows, bias, Y, ldy, accumulate, s);
+  else
+    gemm_generic_dispatch<float>((const float *)W, N, K, X, ldx, rows, bias, Y, ldy, accumulate, s);
+}
+
+// ------------------------------------------------------------------ SwiGLU elementwise
+__global__ void silu_mul_kernel(const float *gate, const float *up, size_t n, float *out) {
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+    out[i] = silu_f(gate[i]) * up[i];
+}
+
+void launch_silu_mul(const float *gate, const float *up, int rows, int f, float *out, hipStream_t s) {
+  const size_t n = (size_t)rows * f;
+  const int blocks = (int)((n + 255) / 256 < 1024 ? (n + 255) / 256 : 1024);
+  silu_mul_kernel<<<blocks, 256, 0, s>>>(gate, up, n, out);
+}
+
+// ------------------------------------------------------------------ argmax (lowest id wins ties)
+__global__ __launch_bounds__(1024) void argmax_kernel(const float *logits, int V, int32_t *out) {
+  __shared__ float bv[16];
+  __shared__ int bi[16];
+  const float *x = logits + (size_t)blockIdx.x * V;
+  float best = -INFINITY;
+  int idx = 0x7fffffff;
+  for (int i = threadIdx.x; i < V; i += 1024) {
+    const float v = x[i];
+    if (v > best) { best = v; idx = i; }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float ov = __shfl_xor(best, o, 64);
+    const int oi = __shfl_xor(idx, o, 64);
+    if (ov > best || (ov == best && oi < idx)) { best = ov; idx = oi; }
+  }
+  if ((threadIdx.x & 63) == 0) { bv[threadIdx.x >> 6] = best; bi[threadIdx.x >> 6] = idx; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 16; ++w)
+      if (bv[w] > best || (bv[w] == best && bi[w] < idx)) { best = bv[w]; idx = bi[w]; }
+    out[blockIdx.x] = idx == 0x7fffffff ? 0 : idx;
+  }
+}
+
+void launch_argmax(const float *logits, int rows, int V, int32_t *out_ids, hipStream_t s) {
+  argmax_kernel<<<rows, 1024, 0, s>>>(logits, V, out_ids);
+}
+
+// ------------------------------------------------------------------ draft head input
+// cat[r] = [feature row r ; embedding of the token that FOLLOWS slot r]  (Sec. 2.2)
+template <typename T>
+__global__ void draft_cat_kernel(const float *feat, int feat_ld, const T *emb, const int32_t *next_ids, int d,
+                                 float *cat) {
+  const int r = blockIdx.x;
+  const T *e = emb + (size_t)next_ids[r] * d;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) {
+    cat[(size_t)r * 2 * d + i] = feat[(size_t)r * feat_ld + i];
+    cat[(size_t)r * 2 * d + d + i] = ld1(e + i);
+  }
+}
+
+void launch_draft_cat(const float *feat, int feat_ld, const void *emb, int dtype, const int32_t *next_ids, int rows,
+                      int d, float *cat, hipStream_t s) {
+  if (dtype == AE_BF16)
+    draft_cat_kernel<bf16_t><<<rows, 256, 0, s>>>(feat, feat_ld, (const bf16_t *)emb, next_ids, d, cat);
+  else
+    draft_cat_kernel<float><<<rows, 256, 0, s>>>(feat, feat_ld, (const float *)emb, next_ids, d, cat);
+}
+
+// ------------------------------------------------------------------ tiny control kernels
+__global__ void pick_draft_kernel(DevState *st, int i) {
+  int32_t t = st->argmax[0];
+  if (st->override_ids[i] >= 0) t = st->override_ids[i];
+  st->draft_ids[i] = t;
+}
+void launch_pick_draft(DevState *st, int i, int32_t *, hipStream_t s) { pick_draft_kernel<<<1, 1, 0, s>>>(st, i); }
+
+__global__ void build_block_kernel(DevState *st, const int32_t *hist, int kv_len, int k) {
+  if (threadIdx.x == 0) st->block[0] = hist[kv_len];
+  if ((int)threadIdx.x < k) st->block[1 + threadIdx.x] = st->draft_ids[threadIdx.x];
+}
+void launch_build_block(DevState *st, const int32_t *hist, int kv_len, int k, hipStream_t s) {
+  build_block_kernel<<<1, 64, 0, s>>>(st, hist, kv_len, k);
+}
+
+// Greedy acceptance (longest draft prefix equal to the target argmax, then the target's
+// own token) and the token-history side of the rollback.
+__global__ void accept_greedy_kernel(DevState *st, int32_t *hist, int kv_len, int rows) {
+  const int k = rows - 1;
+  int acc = 0;
+  while (acc < k && st->block[1 + acc] == st->argmax[acc]) ++acc;
+  const int32_t bonus = st->argmax[acc];
+  for (int i = 0; i <= acc; ++i) hist[kv_len + i] = st->block[i];
+  hist[kv_len + 1 + acc] = bonus;
+  st->n_acc = acc;
+  st->bonus = bonus;
+}
+void launch_accept_greedy(DevState *st, int32_t *hist, int kv_len, int rows, hipStream_t s) {
+  accept_greedy_kernel<<<1, 1, 0, s>>>(st, hist, kv_len, rows);
+}
+
+// ------------------------------------------------------------------ LDLP (Eq. 3)
+// u = [e ; f] (in_mode 0) or f (in_mode 1).  When use_nacc is set the row / slot are
+// taken relative to the acceptance result that an earlier kernel left in *st.
+template <typename T>
+__global__ void ldlp_gather_kernel(const T *emb, const int32_t *hist, const float *F, int d, int in_mode, int slot,
+                                   int f_row, int use_nacc, const DevState *st, float *u) {
+  const int add = use_nacc ? st->n_acc : 0;
+  const float *f = F + (size_t)(f_row + add) * d;
+  if (in_mode == 0) {
+    const T *e = emb + (size_t)hist[slot + add] * d;
+    for (int i = threadIdx.x; i < d; i += blockDim.x) {
+      u[i] = ld1(e + i);
+      u[d + i] = f[i];
+    }
+  } else {
+    for (int i = threadIdx.x; i < d; i += blockDim.x) u[i] = f[i];
+  }
+}
+
+void launch_ldlp_gather(const void *emb, int dtype, const int32_t *hist, const float *F, int d, int in_mode,
+                        int slot, int f_row, const DevState *st_nacc, float *u, hipStream_t s) {
+  const int use = st_nacc != nullptr;
+  if (dtype == AE_BF16)
+    ldlp_gather_kernel<bf16_t><<<1, 1024, 0, s>>>((const bf16_t *)emb, hist, F, d, in_mode, slot, f_row, use, st_nacc, u);
+  else
+    ldlp_gather_kernel<float><<<1, 1024, 0, s>>>((const float *)emb, hist, F, d, in_mode, slot, f_row, use, st_nacc, u);
+}
+
+// z0 = W_in u + b_in comes from the GEMM; here: residual blocks z += silu(W_r z + b_r),
+// y = w_out . silu(z) + b_out, k = clamp(round_half_even(y), 0, k_max).
+template <typename T>
+__global__ __launch_bounds__(1024) void ldlp_tail_kernel(const float *z0, const T *w_res, const float *b_res,
+                                                         const float *w_out, const float *b_out, int h, int n_res,
+                                                         int k_max, DevState *st) {
+  __shared__ float z[kMaxLdlpHidden];
+  __shared__ float t[kMaxLdlpHidden];
+  const int i = threadIdx.x;
+  if (i < h) z[i] = z0[i];
+  __syncthreads();
+  for (int r = 0; r < n_res; ++r) {
+    if (i < h) {
+      const T *row = w_res + ((size_t)r * h + i) * h;
+      float a = 0.f;
+      for (int j = 0; j < h; ++j) a = fmaf(z[j], ld1(row + j), a);
+      t[i] = silu_f(a + b_res[(size_t)r * h + i]);
+    }
+    __syncthreads();
+    if (i < h) z[i] += t[i];
+    __syncthreads();
+  }
+  t[i] = i < h ? silu_f(z[i]) * w_out[i] : 0.f;
+  __syncthreads();
+  for (int o = 512; o > 0; o >>= 1) {  // fixed-shape tree: deterministic
+    if (i < o) t[i] += t[i + o];
+    __syncthreads();
+  }
+  if (i == 0) {
+    const float y = t[0] + b_out[0];
+    float r = rintf(y);  // round half to even
+    if (!(r >= 0.f)) r = 0.f;
+    if (r > (float)k_max) r = (float)k_max;
+    st->y_next = y;
+    st->k_next = (int)r;
+  }
+}
+
+void launch_ldlp_tail(const float *z0, const void *w_res, int dtype, const float *b_res, const float *w_out,
+                      const float *b_out, int h, int n_res, int k_max, DevState *st, hipStream_t s) {
+  if (dtype == AE_BF16)
+    ldlp_tail_kernel<bf16_t><<<1, 1024, 0, s>>>(z0, (const bf16_t *)w_res, b_res, w_out, b_out, h, n_res, k_max, st);
+  else
+    ldlp_tail_kernel<float><<<1, 1024, 0, s>>>(z0, (const float *)w_res, b_res, w_out, b_out, h, n_res, k_max, st);
+}
+
+// ------------------------------------------------------------------ set-up helpers
+// (cos, sin) of pos * base^(-2i/hd), evaluated in double and rounded once to float
+__global__ void rope_table_kernel(float2 *tab, int n_pos, int half, int head_dim, double base) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n_pos * half) return;
+  const int p = idx / half, i = idx % half;
+  const double inv = pow(base, -2.0 * (double)i / (double)head_dim);
+  const double ang = (double)p * inv;
+  tab[idx] = make_float2((float)cos(ang), (float)sin(ang));
+}
+
+void launch_rope_table(float2 *tab, int n_pos, int head_dim, float base, hipStream_t s) {
+  const int half = head_dim / 2, n = n_pos * half;
+  rope_table_kernel<<<(n + 255) / 256, 256, 0, s>>>(tab, n_pos, half, head_dim, (double)base);
+}
+
+__global__ void fill_zero_kernel(uint4 *p, size_t n16) {
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+    p[i] = make_uint4(0, 0, 0, 0);
+}
+
+void launch_fill_zero(void *p, size_t bytes, hipStream_t s) {  // bytes must be a multiple of 16
+  fill_zero_kernel<<<2048, 256, 0, s>>>((uint4 *)p, bytes / 16);
+}
+
+}  // namespace ae
