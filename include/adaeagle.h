@@ -27,7 +27,7 @@
  *    patterns or float); every 1-D vector (norm gains, biases, LDLP output row)
  *    is float.
  *  - Shapes: head_dim in {64, 128}; 1 <= k_max <= 15; with AE_BF16 every matrix
- *    needs out_features % 16 == 0 and in_features % 32 == 0 (else AE_EUNSUPPORTED).
+ *    needs out_features % 16 == 0 and in_features % 256 == 0 (else AE_EUNSUPPORTED).
  */
 #ifndef ADAEAGLE_H
 #define ADAEAGLE_H
@@ -165,6 +165,12 @@ int ae_get_kv_row(ae_ctx *ctx, int layer, int which /*0=K 1=V*/, int slot, float
 typedef struct { float us_ldlp, us_draft, us_verify, us_accept; } ae_phase_times;
 int ae_set_profiling(ae_ctx *ctx, int enabled);
 int ae_get_phase_times(ae_ctx *ctx, ae_phase_times *out);   /* of the last ae_step */
+
+/* Per-kernel timing of the dominant kernel (the fused gate/up SwiGLU GEMM of every decoder
+ * layer): while enabled, each of its launches is bracketed by HIP events on the ctx's
+ * stream; totals are folded in at every stream synchronisation.  Enabling resets them. */
+int ae_set_kernel_timing(ae_ctx *ctx, int enabled);
+int ae_get_kernel_timing(ae_ctx *ctx, double *total_us, int64_t *launches);
 
 const char *ae_version(void);
 

@@ -21,7 +21,7 @@ _CODES = {AE_EINVAL: "AE_EINVAL", AE_ESTATE: "AE_ESTATE", AE_ENOMEM: "AE_ENOMEM"
 EXPORTS = ("ae_init", "ae_free", "ae_last_error", "ae_prefill", "ae_kv_import", "ae_set_state", "ae_ldlp",
            "ae_draft", "ae_verify", "ae_accept", "ae_step", "ae_kv_len", "ae_pending", "ae_get_logits",
            "ae_get_feature", "ae_get_draft_logits", "ae_get_kv_row", "ae_set_profiling", "ae_get_phase_times",
-           "ae_version")
+           "ae_set_kernel_timing", "ae_get_kernel_timing", "ae_version")
 
 
 class AeConfig(C.Structure):
@@ -95,6 +95,8 @@ def load_library(path=LIB_PATH):
         "ae_get_kv_row": (I, [P, I, I, I, f32p]),
         "ae_set_profiling": (I, [P, I]),
         "ae_get_phase_times": (I, [P, C.POINTER(AePhaseTimes)]),
+        "ae_set_kernel_timing": (I, [P, I]),
+        "ae_get_kernel_timing": (I, [P, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
         "ae_version": (C.c_char_p, []),
     }
     for name, (res, args) in sig.items():
@@ -244,6 +246,15 @@ class Engine:
 
     def set_profiling(self, on=True):
         self._chk(self.lib.ae_set_profiling(self.h, int(on)), "ae_set_profiling")
+
+    def set_kernel_timing(self, on=True):
+        self._chk(self.lib.ae_set_kernel_timing(self.h, int(on)), "ae_set_kernel_timing")
+
+    def kernel_timing(self):
+        """(total microseconds, launches) of the gate/up GEMM since timing was enabled."""
+        t, n = C.c_double(), C.c_int64()
+        self._chk(self.lib.ae_get_kernel_timing(self.h, C.byref(t), C.byref(n)), "ae_get_kernel_timing")
+        return t.value, n.value
 
     def phase_times(self):
         t = AePhaseTimes()

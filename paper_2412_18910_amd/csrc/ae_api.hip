@@ -46,25 +46,80 @@ Mat make_mat(const void *p, int N, int K) {
   return m;
 }
 
-// Y[r][n] (+)= X[r][:] . W[n][:] + bias[n]
+// generic path: Y[r][n] (+)= X[r][:] . W[n][:] + bias[n]
 void gemm(ae_ctx *c, const Mat &W, const float *X, int ldx, int rows, const float *bias, float *Y, int ldy,
           int accumulate) {
   launch_gemm_generic(W.rowmajor, c->cfg.dtype, W.N, W.K, X, ldx, rows, bias, Y, ldy, accumulate, c->stream);
 }
 
+bool tileable(const Mat &m) { return m.N % 16 == 0 && m.K % 256 == 0; }
+
+// Allocate a fused k-major tiled matrix and fill it from up to three row-major sources.
+// stride 1: sources stacked ([q;k;v]); stride 2 (two sources): row-blocks interleaved (gate, up).
+int retile_fused(ae_ctx *c, Mat &dst, const Mat *const *src, int nsrc, bool interleave) {
+  int N = 0;
+  for (int i = 0; i < nsrc; ++i) N += src[i]->N;
+  const int K = src[0]->K, NBtot = N / 16;
+  char *p = nullptr;
+  int rc = dev_alloc(c, &p, (size_t)N * K * 2);
+  if (rc) return rc;
+  dst.tiled = p; dst.rowmajor = nullptr; dst.N = N; dst.K = K;
+  int off = 0;
+  for (int i = 0; i < nsrc; ++i) {
+    if (interleave) launch_retile(src[i]->rowmajor, src[i]->N, K, p, NBtot, i, nsrc, c->stream);
+    else launch_retile(src[i]->rowmajor, src[i]->N, K, p, NBtot, off, 1, c->stream);
+    off += src[i]->N / 16;
+  }
+  return AE_OK;
+}
+
 void *kv_layer_ptr(ae_ctx *c, int li) { return (char *)c->kv + (size_t)li * c->kv_layer_stride; }
 
 // One pre-norm decoder layer over `rows` slots starting at pos0; x is updated in place.
-void run_layer(ae_ctx *c, int li, float *x, int rows, int pos0) {
+// next_gain (fast path): RMSNorm gain applied to this layer's output for its consumer (the
+// next layer, the final norm, or nullptr when the consumer takes the raw output).
+void run_layer(ae_ctx *c, int li, float *x, int rows, int pos0, const float *next_gain) {
   const ae_config &g = c->cfg;
   const LayerW &w = c->layers[li];
   const int d = g.d_model, dq = g.n_heads * g.head_dim, dkv = g.n_kv_heads * g.head_dim, f = g.d_ffn;
   hipStream_t s = c->stream;
+  if (c->fast) {
+    // Activations stay in packed (MFMA B-operand) form between kernels.  RMSNorm is split
+    // between producer (x*gain, partial sums of x^2) and consumer (1/rms on accumulators);
+    // SwiGLU and both residual adds are GEMM epilogues.
+    const int Pd = d / 16;
+    GemmLaunch qkv;
+    qkv.W = &w.f_qkv; qkv.Xp = c->xp_a; qkv.rows = rows; qkv.ssq_in = c->ssq_a; qkv.P_in = c->Pa; qkv.eps = g.rms_eps;
+    qkv.epi = EPI_STORE; qkv.nseg = 3;
+    qkv.Y[0] = c->q; qkv.Y[1] = c->kbuf; qkv.Y[2] = c->vbuf;
+    qkv.ldy[0] = dq; qkv.ldy[1] = dkv; qkv.ldy[2] = dkv;
+    qkv.seg_N[0] = dq; qkv.seg_N[1] = dkv; qkv.seg_N[2] = dkv;
+    launch_gemm_mfma(qkv, s);
+    launch_rope_append(c->q, c->kbuf, c->vbuf, rows, pos0, g, c->rope_tab, kv_layer_ptr(c, li), c->kv_v_offset, true, s);
+    launch_attention_mfma(c->q, rows, pos0, g, kv_layer_ptr(c, li), c->kv_v_offset, c->attn_part, c->xp_att, s);
+    GemmLaunch o;
+    o.W = &w.wo; o.Xp = c->xp_att; o.rows = rows; o.epi = EPI_RESID; o.Y[0] = x; o.ldy[0] = d; o.seg_N[0] = d;
+    o.Xp_out = c->xp_f; o.gain_out = w.ffn_norm; o.ssq_out = c->ssq_f;
+    launch_gemm_mfma(o, s);
+    GemmLaunch gu;
+    gu.W = &w.f_gu; gu.Xp = c->xp_f; gu.rows = rows; gu.ssq_in = c->ssq_f; gu.P_in = Pd; gu.eps = g.rms_eps;
+    gu.epi = EPI_SWIGLU; gu.Xp_out = c->xp_h; gu.seg_N[0] = 2 * f;
+    const bool timed = c->ktime && c->kt_used + 2 <= (int)c->kt_ev.size();
+    if (timed) hipEventRecord(c->kt_ev[c->kt_used], s);
+    launch_gemm_mfma(gu, s);
+    if (timed) { hipEventRecord(c->kt_ev[c->kt_used + 1], s); c->kt_used += 2; }
+    GemmLaunch dn;
+    dn.W = &w.w_down; dn.Xp = c->xp_h; dn.rows = rows; dn.epi = EPI_RESID; dn.Y[0] = x; dn.ldy[0] = d; dn.seg_N[0] = d;
+    dn.Xp_out = c->xp_a; dn.gain_out = next_gain; dn.ssq_out = c->ssq_a;
+    launch_gemm_mfma(dn, s);
+    c->Pa = Pd;
+    return;
+  }
   launch_rmsnorm(x, w.attn_norm, rows, d, g.rms_eps, c->xn, s);
   gemm(c, w.wq, c->xn, d, rows, nullptr, c->q, dq, 0);
   gemm(c, w.wk, c->xn, d, rows, nullptr, c->kbuf, dkv, 0);
   gemm(c, w.wv, c->xn, d, rows, nullptr, c->vbuf, dkv, 0);
-  launch_rope_append(c->q, c->kbuf, c->vbuf, rows, pos0, g, c->rope_tab, kv_layer_ptr(c, li), c->kv_v_offset, s);
+  launch_rope_append(c->q, c->kbuf, c->vbuf, rows, pos0, g, c->rope_tab, kv_layer_ptr(c, li), c->kv_v_offset, false, s);
   launch_attention(c->q, rows, pos0, g, kv_layer_ptr(c, li), c->kv_v_offset, c->attn_part, c->att, s);
   gemm(c, w.wo, c->att, dq, rows, nullptr, x, d, 1);
   launch_rmsnorm(x, w.ffn_norm, rows, d, g.rms_eps, c->xn, s);
@@ -79,11 +134,26 @@ void run_layer(ae_ctx *c, int li, float *x, int rows, int pos0) {
 void target_forward(ae_ctx *c, const int32_t *ids_dev, int rows, int pos0, int logit_from) {
   const ae_config &g = c->cfg;
   hipStream_t s = c->stream;
+  const int nr = rows - logit_from;
+  if (c->fast) {
+    launch_embed_packed(c->tok_emb, ids_dev, rows, g.d_model, c->layers[0].attn_norm, c->x, c->xp_a, c->ssq_a, s);
+    c->Pa = 1;
+    for (int l = 0; l < g.n_layers; ++l)
+      run_layer(c, l, c->x, rows, pos0, l + 1 < g.n_layers ? c->layers[l + 1].attn_norm : c->final_norm);
+    launch_rmsnorm(c->x, c->final_norm, rows, g.d_model, g.rms_eps, c->F, s);   // feature rows (LDLP, draft head)
+    if (nr > 0) {
+      GemmLaunch lm;   // final RMSNorm folded into the LM head
+      lm.W = &c->lm_head; lm.Xp = c->xp_a; lm.rows = nr; lm.row0 = logit_from; lm.ssq_in = c->ssq_a; lm.P_in = c->Pa;
+      lm.eps = g.rms_eps; lm.epi = EPI_STORE; lm.Y[0] = c->logits; lm.ldy[0] = g.vocab; lm.seg_N[0] = g.vocab;
+      launch_gemm_mfma(lm, s);
+      launch_argmax(c->logits, nr, g.vocab, c->st->argmax, s);
+    }
+    return;
+  }
   launch_embed(c->tok_emb, g.dtype, ids_dev, rows, g.d_model, c->x, s);
-  for (int l = 0; l < g.n_layers; ++l) run_layer(c, l, c->x, rows, pos0);
+  for (int l = 0; l < g.n_layers; ++l) run_layer(c, l, c->x, rows, pos0, nullptr);
   launch_rmsnorm(c->x, c->final_norm, rows, g.d_model, g.rms_eps, c->F, s);
-  if (logit_from < rows) {
-    const int nr = rows - logit_from;
+  if (nr > 0) {
     gemm(c, c->lm_head, c->F + (size_t)logit_from * g.d_model, g.d_model, nr, nullptr, c->logits, g.vocab, 0);
     launch_argmax(c->logits, nr, g.vocab, c->st->argmax, s);
   }
@@ -94,9 +164,36 @@ void target_forward(ae_ctx *c, const int32_t *ids_dev, int rows, int pos0, int l
 void draft_rows(ae_ctx *c, const float *feat, int feat_ld, const int32_t *next_ids_dev, int rows, int slot0) {
   const ae_config &g = c->cfg;
   hipStream_t s = c->stream;
+  const LayerW &dl = c->layers[g.n_layers];
+  if (c->fast) {
+    launch_draft_cat_packed(feat, feat_ld, c->tok_emb, next_ids_dev, rows, g.d_model, c->xp_cat, s);
+    GemmLaunch fc;
+    fc.W = &c->draft_fc; fc.Xp = c->xp_cat; fc.rows = rows; fc.epi = EPI_STORE; fc.bias = c->draft_fc_b;
+    fc.Y[0] = c->x; fc.ldy[0] = g.d_model; fc.seg_N[0] = g.d_model;
+    fc.Xp_out = c->xp_a; fc.gain_out = dl.attn_norm; fc.ssq_out = c->ssq_a;
+    launch_gemm_mfma(fc, s);
+    c->Pa = g.d_model / 16;
+    run_layer(c, g.n_layers, c->x, rows, slot0, nullptr);   // leaves packed(raw output) in xp_a
+    return;
+  }
   launch_draft_cat(feat, feat_ld, c->tok_emb, g.dtype, next_ids_dev, rows, g.d_model, c->cat, s);
   gemm(c, c->draft_fc, c->cat, 2 * g.d_model, rows, c->draft_fc_b, c->x, g.d_model, 0);
-  run_layer(c, g.n_layers, c->x, rows, slot0);
+  run_layer(c, g.n_layers, c->x, rows, slot0, nullptr);
+}
+
+// LM head (shared with the target) on draft-head output row `row` -> dlogits[i], argmax
+void draft_lm_head(ae_ctx *c, int row, int i) {
+  const ae_config &g = c->cfg;
+  float *dl = c->dlogits + (size_t)i * g.vocab;
+  if (c->fast) {
+    GemmLaunch lm;
+    lm.W = &c->lm_head; lm.Xp = c->xp_a; lm.rows = 1; lm.row0 = row; lm.epi = EPI_STORE;
+    lm.Y[0] = dl; lm.ldy[0] = g.vocab; lm.seg_N[0] = g.vocab;
+    launch_gemm_mfma(lm, c->stream);
+  } else {
+    gemm(c, c->lm_head, c->x + (size_t)row * g.d_model, g.d_model, 1, nullptr, dl, g.vocab, 0);
+  }
+  launch_argmax(dl, 1, g.vocab, c->st->argmax, c->stream);
 }
 
 void enqueue_ldlp(ae_ctx *c, int slot, int f_row, bool relative_to_accept) {
@@ -111,10 +208,23 @@ void enqueue_ldlp(ae_ctx *c, int slot, int f_row, bool relative_to_accept) {
                    g.ldlp_n_res, g.k_max, c->st, s);
 }
 
+// after a stream synchronisation: fold the finished event pairs into the totals
+void drain_kernel_timing(ae_ctx *c) {
+  for (int i = 0; i + 1 < c->kt_used; i += 2) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, c->kt_ev[i], c->kt_ev[i + 1]) == hipSuccess) {
+      c->kt_total_us += (double)ms * 1e3;
+      c->kt_count += 1;
+    }
+  }
+  c->kt_used = 0;
+}
+
 int read_state(ae_ctx *c) {
   HIPCHK(c, hipMemcpyAsync(c->h_st, c->st, sizeof(DevState), hipMemcpyDeviceToHost, c->stream));
   HIPCHK(c, hipStreamSynchronize(c->stream));
   HIPCHK(c, hipGetLastError());
+  if (c->kt_used) drain_kernel_timing(c);
   return AE_OK;
 }
 
@@ -188,6 +298,56 @@ int ae_init(const ae_config *cfg, const ae_weights *w, void *hip_stream, ae_ctx 
   c->ldlp_b_in = w->ldlp_b_in; c->ldlp_w_res = w->ldlp_w_res; c->ldlp_b_res = w->ldlp_b_res;
   c->ldlp_w_out = w->ldlp_w_out; c->ldlp_b_out = w->ldlp_b_out;
 
+  // bf16: re-tile every streamed matrix into the MFMA operand layout (see kernels_mfma.hip)
+  c->fast = g.dtype == AE_BF16 && !getenv("AE_FORCE_GENERIC");
+  if (c->fast) {
+    bool ok = tileable(c->lm_head) && tileable(c->draft_fc) && g.head_dim % 32 == 0;
+    for (auto &l : c->layers)
+      ok = ok && tileable(l.wq) && tileable(l.wk) && tileable(l.wv) && tileable(l.wo) && tileable(l.w_gate) &&
+           tileable(l.w_up) && tileable(l.w_down);
+    if (!ok) {
+      c->err = "bf16 matrices need out_features % 16 == 0 and in_features % 256 == 0";
+      return bail(AE_EUNSUPPORTED);
+    }
+    const Mat *one[1];
+    one[0] = &c->lm_head;
+    Mat lm = c->lm_head;
+    if ((rc = retile_fused(c, lm, one, 1, false))) return bail(rc);
+    c->lm_head.tiled = lm.tiled;
+    one[0] = &c->draft_fc;
+    Mat fc = c->draft_fc;
+    if ((rc = retile_fused(c, fc, one, 1, false))) return bail(rc);
+    c->draft_fc.tiled = fc.tiled;
+    for (auto &l : c->layers) {
+      const Mat *qkv[3] = {&l.wq, &l.wk, &l.wv};
+      const Mat *gu[2] = {&l.w_gate, &l.w_up};
+      Mat t;
+      if ((rc = retile_fused(c, l.f_qkv, qkv, 3, false)) || (rc = retile_fused(c, l.f_gu, gu, 2, true))) return bail(rc);
+      one[0] = &l.wo; t = l.wo;
+      if ((rc = retile_fused(c, t, one, 1, false))) return bail(rc);
+      l.wo.tiled = t.tiled;
+      one[0] = &l.w_down; t = l.w_down;
+      if ((rc = retile_fused(c, t, one, 1, false))) return bail(rc);
+      l.w_down.tiled = t.tiled;
+    }
+    // packed activation buffers: K * 64 bytes each (hi + lo, 16 row slots)
+    const size_t dqq = (size_t)g.n_heads * g.head_dim;
+    char *pa = nullptr, *pf = nullptr, *pt = nullptr, *ph = nullptr, *pc = nullptr;
+    if ((rc = dev_alloc(c, &pa, (size_t)g.d_model * 64)) || (rc = dev_alloc(c, &pf, (size_t)g.d_model * 64)) ||
+        (rc = dev_alloc(c, &pt, dqq * 64)) || (rc = dev_alloc(c, &ph, (size_t)g.d_ffn * 64)) ||
+        (rc = dev_alloc(c, &pc, (size_t)2 * g.d_model * 64)) ||
+        (rc = dev_alloc(c, &c->ssq_a, (size_t)g.d_model)) || (rc = dev_alloc(c, &c->ssq_f, (size_t)g.d_model)))
+      return bail(rc);
+    c->xp_a = pa; c->xp_f = pf; c->xp_att = pt; c->xp_h = ph; c->xp_cat = pc;
+    launch_fill_zero(pa, (size_t)g.d_model * 64, c->stream);
+    launch_fill_zero(pf, (size_t)g.d_model * 64, c->stream);
+    launch_fill_zero(pt, dqq * 64, c->stream);
+    launch_fill_zero(ph, (size_t)g.d_ffn * 64, c->stream);
+    launch_fill_zero(pc, (size_t)2 * g.d_model * 64, c->stream);
+    launch_fill_zero(c->ssq_a, (size_t)g.d_model * 4, c->stream);
+    launch_fill_zero(c->ssq_f, (size_t)g.d_model * 4, c->stream);
+  }
+
   // KV cache for n_layers target layers + the draft layer, zero-filled so that slots that
   // were never written hold finite values
   c->kv_layer_stride = kv_layer_bytes(g);
@@ -239,6 +399,7 @@ void ae_free(ae_ctx *c) {
   if (c->h_ids) hipHostFree(c->h_ids);
   for (auto &e : c->ev)
     if (e) hipEventDestroy(e);
+  for (auto &e : c->kt_ev) hipEventDestroy(e);
   delete c;
 }
 
@@ -287,7 +448,7 @@ int ae_kv_import(ae_ctx *c, int layer, const float *k, const float *v, int n) {
   hipError_t e = hipMemcpy(tmp, k, cnt * sizeof(float), hipMemcpyHostToDevice);
   if (e == hipSuccess) e = hipMemcpy(tmp + cnt, v, cnt * sizeof(float), hipMemcpyHostToDevice);
   if (e == hipSuccess) {
-    launch_kv_import(kv_layer_ptr(c, layer), c->kv_v_offset, g, tmp, tmp + cnt, n, c->stream);
+    launch_kv_import(kv_layer_ptr(c, layer), c->kv_v_offset, g, tmp, tmp + cnt, n, c->fast, c->stream);
     e = hipStreamSynchronize(c->stream);
   }
   hipFree(tmp);
@@ -347,14 +508,14 @@ int ae_draft(ae_ctx *c, int k, const int32_t *override_ids, const double *u_draf
   draft_rows(c, c->F + (size_t)(c->nF - catch_rows) * g.d_model, g.d_model, c->hist + c->dlen + 1, catch_rows, c->dlen);
   c->dlen = n;
   const float *fh = c->x + (size_t)(catch_rows - 1) * g.d_model;
+  int fh_row = catch_rows - 1;
   for (int i = 0; i < k; ++i) {
     if (i > 0) {  // chain: the head's previous output replaces the feature
       draft_rows(c, fh, g.d_model, c->st->draft_ids + (i - 1), 1, n - 1 + i);
       fh = c->x;
+      fh_row = 0;
     }
-    float *dl = c->dlogits + (size_t)i * g.vocab;
-    gemm(c, c->lm_head, fh, g.d_model, 1, nullptr, dl, g.vocab, 0);
-    launch_argmax(dl, 1, g.vocab, c->st->argmax, s);
+    draft_lm_head(c, fh_row, i);
     launch_pick_draft(c->st, i, nullptr, s);
   }
   c->cur_k = k;
@@ -488,8 +649,35 @@ int ae_get_kv_row(ae_ctx *c, int layer, int which, int slot, float *out) {
   const ae_config &g = c->cfg;
   if (!out || layer < 0 || layer > g.n_layers || (which != 0 && which != 1) || slot < 0 || slot >= g.n_ctx_max)
     return fail(c, AE_EINVAL, "ae_get_kv_row: argument out of range");
-  launch_kv_export(kv_layer_ptr(c, layer), c->kv_v_offset, g, which, slot, c->attn_part, c->stream);
+  launch_kv_export(kv_layer_ptr(c, layer), c->kv_v_offset, g, which, slot, c->attn_part, c->fast, c->stream);
   return copy_out(c, c->attn_part, (size_t)g.n_kv_heads * g.head_dim, out);
+}
+
+int ae_set_kernel_timing(ae_ctx *c, int enabled) {
+  if (!c) return AE_EINVAL;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  if (enabled && c->kt_ev.empty()) {
+    // enough pairs for every decoder layer of one step (k_max+1 draft forwards + verify)
+    const int pairs = (c->cfg.n_layers + c->cfg.k_max + 2) * 2;
+    for (int i = 0; i < 2 * pairs; ++i) {
+      hipEvent_t e;
+      HIPCHK(c, hipEventCreate(&e));
+      c->kt_ev.push_back(e);
+    }
+  }
+  drain_kernel_timing(c);
+  c->ktime = enabled != 0;
+  c->kt_total_us = 0.0;
+  c->kt_count = 0;
+  return AE_OK;
+}
+
+int ae_get_kernel_timing(ae_ctx *c, double *total_us, int64_t *launches) {
+  if (!c) return AE_EINVAL;
+  if (!total_us || !launches) return fail(c, AE_EINVAL, "ae_get_kernel_timing: NULL output");
+  *total_us = c->kt_total_us;
+  *launches = c->kt_count;
+  return AE_OK;
 }
 
 int ae_set_profiling(ae_ctx *c, int enabled) {

@@ -40,6 +40,7 @@ struct Mat {
 struct LayerW {
   const float *attn_norm = nullptr, *ffn_norm = nullptr;
   Mat wq, wk, wv, wo, w_gate, w_up, w_down;
+  Mat f_qkv, f_gu;   // bf16 fast path: fused tiled [q;k;v] and row-block-interleaved [gate,up]
 };
 
 }  // namespace ae
@@ -77,6 +78,10 @@ struct ae_ctx {
   float *dlogits = nullptr;        // [k_max][V]
   float *attn_part = nullptr;      // split-KV partials
   float *ldlp_u = nullptr, *ldlp_z = nullptr;
+  // bf16 fast path: packed activations (GEMM B operands) and RMSNorm partial sums
+  void *xp_a = nullptr, *xp_f = nullptr, *xp_att = nullptr, *xp_h = nullptr, *xp_cat = nullptr;
+  float *ssq_a = nullptr, *ssq_f = nullptr;
+  int Pa = 0;                      // number of valid partial-sum rows in ssq_a
   double *prob = nullptr;          // T>0 scratch [2][V]
   int32_t *hist = nullptr;         // device token history by slot
   ae::DevState *st = nullptr;      // device state
@@ -92,6 +97,13 @@ struct ae_ctx {
   float y_next = 0.f;
   std::vector<int32_t> h_hist;     // host mirror of the token history
   std::vector<int32_t> h_block;
+
+  // per-kernel event timing of the gate/up GEMM launches (see ae_set_kernel_timing)
+  bool ktime = false;
+  std::vector<hipEvent_t> kt_ev;   // pairs (begin, end)
+  int kt_used = 0;
+  double kt_total_us = 0.0;
+  long long kt_count = 0;
 
   // profiling
   bool profiling = false;
@@ -124,14 +136,19 @@ void launch_fill_zero(void *p, size_t bytes, hipStream_t s);
 // ---- attention (kernels_attn.hip) ----
 size_t kv_layer_bytes(const ae_config &c);
 size_t kv_v_offset_bytes(const ae_config &c);
+int kv_capacity(const ae_config &c);   // n_ctx_max rounded up to a whole attention chunk
 void launch_rope_append(float *q, const float *k, const float *v, int rows, int pos0, const ae_config &c,
-                        const float2 *rope_tab, void *kv_layer, size_t v_off, hipStream_t s);
+                        const float2 *rope_tab, void *kv_layer, size_t v_off, bool tiled, hipStream_t s);
+void launch_attn_merge(const float *part, int rows, const ae_config &c, int n_chunks, float *out, hipStream_t s);
+// bf16 MFMA attention over the tiled cache layout (kernels_attn_mfma.hip)
+void launch_attention_mfma(const float *q, int rows, int pos0, const ae_config &c, const void *kv_layer, size_t v_off,
+                           float *part, void *Xp_out, hipStream_t s);
 void launch_attention(const float *q, int rows, int pos0, const ae_config &c, const void *kv_layer, size_t v_off,
                       float *part, float *out, hipStream_t s);
 void launch_kv_import(void *kv_layer, size_t v_off, const ae_config &c, const float *k_dev, const float *v_dev, int n,
-                      hipStream_t s);
+                      bool tiled, hipStream_t s);
 void launch_kv_export(const void *kv_layer, size_t v_off, const ae_config &c, int which, int slot, float *out_dev,
-                      hipStream_t s);
+                      bool tiled, hipStream_t s);
 size_t attn_part_floats(const ae_config &c);
 
 // ---- T > 0 sampling (kernels_sample.hip) ----
@@ -140,6 +157,32 @@ void launch_accept_sample(const float *tl, const float *dl, int V, int k, float 
                           int kv_len, double *prob, hipStream_t s);
 
 // ---- bf16 MFMA path (kernels_mfma.hip) ----
-void launch_retile(const void *rowmajor, int N, int K, void *tiled, hipStream_t s);
+// Row-block nb of a row-major [N,K] matrix -> row-block nb_off + nb*nb_stride of a fused
+// k-major tiled matrix with NBtot row-blocks.
+void launch_retile(const void *rowmajor, int N, int K, void *tiled, int NBtot, int nb_off, int nb_stride, hipStream_t s);
+enum { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
+struct GemmLaunch {
+  const Mat *W = nullptr;         // fused tiled matrix: N = all output rows, K
+  const void *Xp = nullptr;       // packed activations
+  int rows = 0, row0 = 0;         // output row m reads packed row row0 + m
+  const float *ssq_in = nullptr;  // != nullptr: fused RMSNorm, [P_in][16] partial sums of x^2
+  int P_in = 0;
+  float eps = 0.f;
+  const float *bias = nullptr;
+  int epi = EPI_STORE;
+  int nseg = 1;                   // output segments (q | k | v)
+  float *Y[3] = {nullptr, nullptr, nullptr};
+  int ldy[3] = {0, 0, 0};
+  int seg_N[3] = {0, 0, 0};
+  void *Xp_out = nullptr;         // packed output for the next GEMM
+  const float *gain_out = nullptr;
+  float *ssq_out = nullptr;
+};
+void launch_gemm_mfma(const GemmLaunch &L, hipStream_t s);
+void launch_embed_packed(const void *emb, const int32_t *ids_dev, int rows, int d, const float *gain, float *x,
+                         void *Xp, float *ssq, hipStream_t s);
+void launch_pack_rows(const float *src, int ld, int rows, int K, const float *gain, void *Xp, hipStream_t s);
+void launch_draft_cat_packed(const float *feat, int feat_ld, const void *emb, const int32_t *next_ids, int rows, int d,
+                             void *Xp, hipStream_t s);
 
 }  // namespace ae

@@ -31,16 +31,26 @@ template <> __device__ __forceinline__ float cvt_out<float>(float v) { return v;
 template <> __device__ __forceinline__ bf16_t cvt_out<bf16_t>(float v) { return f2bf_(v); }
 
 static size_t esize(const ae_config &c) { return c.dtype == AE_BF16 ? 2 : 4; }
+int kv_capacity(const ae_config &c) { return (c.n_ctx_max + kAttnChunk - 1) / kAttnChunk * kAttnChunk; }
 size_t kv_v_offset_bytes(const ae_config &c) {
-  return (size_t)c.n_kv_heads * c.head_dim * c.n_ctx_max * esize(c);
+  return (size_t)c.n_kv_heads * c.head_dim * kv_capacity(c) * esize(c);
 }
 size_t kv_layer_bytes(const ae_config &c) { return 2 * kv_v_offset_bytes(c); }
 
+// Element index of K[kh][slot][d] / V[kh][slot][d] in the cache of one layer.  n_ctx is
+// the capacity (a multiple of kAttnChunk).  `tiled` selects the MFMA operand layout
+// of kernels_attn_mfma.hip, else the layout described at the top of this file.
 template <typename T>
-__device__ __forceinline__ size_t k_index(int kh, int d, int slot, int hd, int n_ctx) {
+__device__ __forceinline__ size_t k_index(int kh, int d, int slot, int hd, int n_ctx, bool tiled) {
+  if (tiled)  // [kh][slot/16][d/32][lane = ((d%32)/8)*16 + slot%16][d%8]
+    return ((((size_t)kh * (n_ctx / 16) + (slot >> 4)) * (hd / 32) + (d >> 5)) * 64 + ((d & 31) >> 3) * 16 + (slot & 15)) * 8 + (d & 7);
   return (((size_t)kh * (hd / 8) + (d >> 3)) * n_ctx + slot) * 8 + (d & 7);
 }
-__device__ __forceinline__ size_t v_index(int kh, int d, int slot, int hd, int n_ctx) {
+__device__ __forceinline__ size_t v_index(int kh, int d, int slot, int hd, int n_ctx, bool tiled) {
+  if (tiled) {  // [kh][slot/32][d/16][lane = ((slot%16)/4)*16 + d%16][e = slot%4 + 4*((slot%32)/16)]
+    const int w16 = slot & 15, half = (slot & 31) >> 4;
+    return ((((size_t)kh * (n_ctx / 32) + (slot >> 5)) * (hd / 16) + (d >> 4)) * 64 + (w16 >> 2) * 16 + (d & 15)) * 8 + (w16 & 3) + 4 * half;
+  }
   return ((size_t)kh * n_ctx + slot) * hd + d;
 }
 
@@ -48,7 +58,7 @@ __device__ __forceinline__ size_t v_index(int kh, int d, int slot, int hd, int n
 // grid (rows, H + 2*Hkv), block hd/2.  Rotate-half pairing (i, i + hd/2).
 template <typename T>
 __global__ void rope_append_kernel(float *q, const float *k, const float *v, int pos0, int H, int Hkv, int hd,
-                                   int n_ctx, const float2 *tab, T *Kc, T *Vc) {
+                                   int n_ctx, bool tiled, const float2 *tab, T *Kc, T *Vc) {
   const int r = blockIdx.x, hs = blockIdx.y, i = threadIdx.x, half = hd / 2;
   const int slot = pos0 + r;
   const float2 cs = tab[(size_t)slot * half + i];
@@ -61,26 +71,26 @@ __global__ void rope_append_kernel(float *q, const float *k, const float *v, int
     const int kh = hs - H;
     const float *p = k + ((size_t)r * Hkv + kh) * hd;
     const float a = p[i], b = p[i + half];
-    Kc[k_index<T>(kh, i, slot, hd, n_ctx)] = cvt_out<T>(a * cs.x - b * cs.y);
-    Kc[k_index<T>(kh, i + half, slot, hd, n_ctx)] = cvt_out<T>(b * cs.x + a * cs.y);
+    Kc[k_index<T>(kh, i, slot, hd, n_ctx, tiled)] = cvt_out<T>(a * cs.x - b * cs.y);
+    Kc[k_index<T>(kh, i + half, slot, hd, n_ctx, tiled)] = cvt_out<T>(b * cs.x + a * cs.y);
   } else {
     const int kh = hs - H - Hkv;
     const float *p = v + ((size_t)r * Hkv + kh) * hd;
-    Vc[v_index(kh, i, slot, hd, n_ctx)] = cvt_out<T>(p[i]);
-    Vc[v_index(kh, i + half, slot, hd, n_ctx)] = cvt_out<T>(p[i + half]);
+    Vc[v_index(kh, i, slot, hd, n_ctx, tiled)] = cvt_out<T>(p[i]);
+    Vc[v_index(kh, i + half, slot, hd, n_ctx, tiled)] = cvt_out<T>(p[i + half]);
   }
 }
 
 void launch_rope_append(float *q, const float *k, const float *v, int rows, int pos0, const ae_config &c,
-                        const float2 *rope_tab, void *kv_layer, size_t v_off, hipStream_t s) {
+                        const float2 *rope_tab, void *kv_layer, size_t v_off, bool tiled, hipStream_t s) {
   const dim3 grid(rows, c.n_heads + 2 * c.n_kv_heads);
   void *vc = (char *)kv_layer + v_off;
   if (c.dtype == AE_BF16)
     rope_append_kernel<bf16_t><<<grid, c.head_dim / 2, 0, s>>>(q, k, v, pos0, c.n_heads, c.n_kv_heads, c.head_dim,
-                                                               c.n_ctx_max, rope_tab, (bf16_t *)kv_layer, (bf16_t *)vc);
+                                                               kv_capacity(c), tiled, rope_tab, (bf16_t *)kv_layer, (bf16_t *)vc);
   else
     rope_append_kernel<float><<<grid, c.head_dim / 2, 0, s>>>(q, k, v, pos0, c.n_heads, c.n_kv_heads, c.head_dim,
-                                                              c.n_ctx_max, rope_tab, (float *)kv_layer, (float *)vc);
+                                                              kv_capacity(c), tiled, rope_tab, (float *)kv_layer, (float *)vc);
 }
 
 // ------------------------------------------------------------------ attention, split-KV partials
@@ -245,8 +255,15 @@ __global__ void attn_merge_kernel(const float *part, int rows, int H, int Hkv, i
 }
 
 size_t attn_part_floats(const ae_config &c) {
-  const int max_chunks = (c.n_ctx_max + kAttnChunk - 1) / kAttnChunk;
+  const int max_chunks = kv_capacity(c) / kAttnChunk;
   return (size_t)c.n_heads * max_chunks * kMaxRows * (c.head_dim + 2);
+}
+
+void launch_attn_merge(const float *part, int rows, const ae_config &c, int n_chunks, float *out, hipStream_t s) {
+  if (c.head_dim == 128)
+    attn_merge_kernel<128><<<rows * c.n_heads, 128, 0, s>>>(part, rows, c.n_heads, c.n_kv_heads, n_chunks, out);
+  else
+    attn_merge_kernel<64><<<rows * c.n_heads, 64, 0, s>>>(part, rows, c.n_heads, c.n_kv_heads, n_chunks, out);
 }
 
 void launch_attention(const float *q, int rows, int pos0, const ae_config &c, const void *kv_layer, size_t v_off,
@@ -261,7 +278,7 @@ void launch_attention(const float *q, int rows, int pos0, const ae_config &c, co
   if (sm > 48 * 1024)                                                                                          \
     (void)hipFuncSetAttribute((const void *)attn_partial_kernel<T, HD>, hipFuncAttributeMaxDynamicSharedMemorySize, \
                               (int)sm);                                                                        \
-  attn_partial_kernel<T, HD><<<grid, 256, sm, s>>>(q, rows, pos0, c.n_heads, c.n_kv_heads, c.n_ctx_max,         \
+  attn_partial_kernel<T, HD><<<grid, 256, sm, s>>>(q, rows, pos0, c.n_heads, c.n_kv_heads, kv_capacity(c),      \
                                                    (const T *)kv_layer, (const T *)vc, part, scale);            \
   attn_merge_kernel<HD><<<rows * c.n_heads, HD, 0, s>>>(part, rows, c.n_heads, c.n_kv_heads, n_chunks, out);
   if (c.dtype == AE_BF16) {
@@ -274,43 +291,45 @@ void launch_attention(const float *q, int rows, int pos0, const ae_config &c, co
 
 // ------------------------------------------------------------------ import / export (tests, set-up)
 template <typename T>
-__global__ void kv_import_kernel(T *Kc, T *Vc, const float *k, const float *v, int n, int Hkv, int hd, int n_ctx) {
+__global__ void kv_import_kernel(T *Kc, T *Vc, const float *k, const float *v, int n, int Hkv, int hd, int n_ctx,
+                                 bool tiled) {
   const size_t total = (size_t)n * Hkv * hd;
   for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
     const int d = i % hd, kh = (i / hd) % Hkv, slot = i / ((size_t)hd * Hkv);
-    Kc[k_index<T>(kh, d, slot, hd, n_ctx)] = cvt_out<T>(k[i]);
-    Vc[v_index(kh, d, slot, hd, n_ctx)] = cvt_out<T>(v[i]);
+    Kc[k_index<T>(kh, d, slot, hd, n_ctx, tiled)] = cvt_out<T>(k[i]);
+    Vc[v_index(kh, d, slot, hd, n_ctx, tiled)] = cvt_out<T>(v[i]);
   }
 }
 
 void launch_kv_import(void *kv_layer, size_t v_off, const ae_config &c, const float *k_dev, const float *v_dev, int n,
-                      hipStream_t s) {
+                      bool tiled, hipStream_t s) {
   void *vc = (char *)kv_layer + v_off;
   if (c.dtype == AE_BF16)
     kv_import_kernel<bf16_t><<<1024, 256, 0, s>>>((bf16_t *)kv_layer, (bf16_t *)vc, k_dev, v_dev, n, c.n_kv_heads,
-                                                  c.head_dim, c.n_ctx_max);
+                                                  c.head_dim, kv_capacity(c), tiled);
   else
     kv_import_kernel<float><<<1024, 256, 0, s>>>((float *)kv_layer, (float *)vc, k_dev, v_dev, n, c.n_kv_heads,
-                                                 c.head_dim, c.n_ctx_max);
+                                                 c.head_dim, kv_capacity(c), tiled);
 }
 
 template <typename T>
-__global__ void kv_export_kernel(const T *Kc, const T *Vc, int which, int slot, int Hkv, int hd, int n_ctx, float *out) {
+__global__ void kv_export_kernel(const T *Kc, const T *Vc, int which, int slot, int Hkv, int hd, int n_ctx, bool tiled,
+                                 float *out) {
   for (int i = threadIdx.x; i < Hkv * hd; i += blockDim.x) {
     const int d = i % hd, kh = i / hd;
-    out[i] = which ? cvt_in<T>(Vc[v_index(kh, d, slot, hd, n_ctx)]) : cvt_in<T>(Kc[k_index<T>(kh, d, slot, hd, n_ctx)]);
+    out[i] = which ? cvt_in<T>(Vc[v_index(kh, d, slot, hd, n_ctx, tiled)]) : cvt_in<T>(Kc[k_index<T>(kh, d, slot, hd, n_ctx, tiled)]);
   }
 }
 
 void launch_kv_export(const void *kv_layer, size_t v_off, const ae_config &c, int which, int slot, float *out_dev,
-                      hipStream_t s) {
+                      bool tiled, hipStream_t s) {
   const void *vc = (const char *)kv_layer + v_off;
   if (c.dtype == AE_BF16)
     kv_export_kernel<bf16_t><<<1, 256, 0, s>>>((const bf16_t *)kv_layer, (const bf16_t *)vc, which, slot, c.n_kv_heads,
-                                               c.head_dim, c.n_ctx_max, out_dev);
+                                               c.head_dim, kv_capacity(c), tiled, out_dev);
   else
     kv_export_kernel<float><<<1, 256, 0, s>>>((const float *)kv_layer, (const float *)vc, which, slot, c.n_kv_heads,
-                                              c.head_dim, c.n_ctx_max, out_dev);
+                                              c.head_dim, kv_capacity(c), tiled, out_dev);
 }
 
 }  // namespace ae

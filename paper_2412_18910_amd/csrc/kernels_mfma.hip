@@ -1,0 +1,321 @@
+// Skinny bf16 GEMMs of the decode step on the gfx950 matrix cores.
+//
+//   Y[m][n] = epilogue( sum_k X[m][k] * W[n][k] ),  m < rows <= 16,  W bf16.
+//
+// These GEMMs are HBM-bound: every weight byte is read exactly once per call and the
+// whole job is to keep the memory system saturated.  Design:
+//  * Weights are re-tiled once (ae_init) into the A-operand layout of
+//    v_mfma_f32_16x16x32_bf16: a tile = 16 output rows x 32 k = 1 KB whose 16-byte piece
+//    `lane` is what lane (lane%16 = row, lane/16 = k-octet) feeds to the instruction, so a
+//    wave-wide 128-bit load is one coalesced 1 KB burst with no LDS staging.  Tiles are
+//    stored k-major, tile (nb, kt) at index kt*NB + nb: the row-blocks a workgroup owns
+//    are contiguous for every kt and neighbouring workgroups read neighbouring memory,
+//    which measured ~25% faster than strip-major storage on MI355X.
+//  * Activations travel between kernels already in B-operand form ("packed"): for every
+//    k-tile two 1 KB tiles (bf16 hi, bf16 lo; x ~= hi + lo keeps 16 significant bits),
+//    lane = (k-octet)*16 + row.  Producers (embedding, GEMM epilogues, attention merge)
+//    write this form, so the GEMM hot loop is only loads and MFMAs (two per weight tile).
+//  * A workgroup owns NACC adjacent row-blocks and splits K over its NW waves; every wave
+//    runs a register ring of D k-tiles (loads for tile t+D are issued when tile t is
+//    consumed), then the waves' partial tiles are summed through LDS in a fixed order.
+//    No atomics; column m of a tile never mixes with another column, so a row's result
+//    is independent of the number of rows in the block.
+//  * RMSNorm is folded in: the producer stores x*gain (packed) and per-row-block partial
+//    sums of x^2; the consumer sums the partials in a fixed order and scales its
+//    accumulators by 1/rms.  Epilogues: store(+bias), residual add, SwiGLU (gate and up
+//    tiles interleaved in the matrix), each optionally emitting the packed form (and the
+//    x^2 partials) for the next GEMM.
+#include "ae_internal.h"
+#include "packed.h"
+
+namespace ae {
+
+// ------------------------------------------------------------------ re-tiling (set-up)
+// Row-block nb of a row-major [N,K] bf16 matrix goes to row-block (nb_off + nb*nb_stride)
+// of a fused k-major tiled matrix with NBtot row-blocks.
+__global__ void retile_kernel(const uint4 *src, uint4 *dst, int NB, int KT, int NBtot, int nb_off, int nb_stride) {
+  const size_t total = (size_t)NB * KT * 64;
+  for (size_t o = blockIdx.x * (size_t)blockDim.x + threadIdx.x; o < total; o += (size_t)gridDim.x * blockDim.x) {
+    const int lane = o & 63;
+    const size_t tile = o >> 6;
+    const int nb = tile % NB;
+    const size_t kt = tile / NB;
+    const size_t row = (size_t)nb * 16 + (lane & 15);
+    dst[(kt * NBtot + nb_off + (size_t)nb * nb_stride) * 64 + lane] = src[row * (size_t)(KT * 4) + kt * 4 + (lane >> 4)];
+  }
+}
+
+void launch_retile(const void *rowmajor, int N, int K, void *tiled, int NBtot, int nb_off, int nb_stride, hipStream_t s) {
+  retile_kernel<<<2048, 256, 0, s>>>((const uint4 *)rowmajor, (uint4 *)tiled, N / 16, K / 32, NBtot, nb_off, nb_stride);
+}
+
+// ------------------------------------------------------------------ GEMM
+__device__ __forceinline__ float silu_dev(float x) { return x / (1.0f + expf(-x)); }
+
+struct GemmSeg {
+  float *Y;     // float destination of this range of row-blocks
+  int ldy;
+  int nb_end;   // exclusive end of the range in fused row-block indices
+};
+
+struct GemmArgs {
+  const u32x4 *W;       // fused k-major tiled matrix
+  const u32x4 *Xp;      // packed activations [KT][2][64]
+  const float *ssq_in;  // NORM: [P_in][16] partial sums of x^2
+  const float *bias;    // [N] or nullptr (EPI_STORE, segment 0)
+  u32x4 *Xp_out;        // packed output for the next GEMM (nullable)
+  const float *gain_out;  // gain folded into Xp_out (nullable = 1)
+  float *ssq_out;       // [NBtot][16] partial sums of the new x^2 (nullable)
+  GemmSeg seg[3];
+  int NBtot, KT, rows, row0, P_in;   // output row m reads packed row row0 + m
+  float eps;
+};
+
+template <int EPI, bool NORM, int NACC, int NW, int D>
+__global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(const GemmArgs a) {
+  __shared__ f32x4 red[NW][NACC][64];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int g = lane >> 4, m = lane & 15;
+  // a workgroup hanging over the end of the matrix slides back (recomputes, stores nothing new)
+  const int nb0 = min((int)blockIdx.x * NACC, a.NBtot - NACC);
+  const bool row_ok = m < a.rows;
+  const int xrow = a.row0 + (row_ok ? m : a.rows - 1);    // rows beyond the block re-read the last row
+  const int xlane = g * 16 + xrow;
+
+  const u32x4 *wp = a.W + (size_t)nb0 * 64 + lane;
+  const size_t kstride = (size_t)a.NBtot * 64;
+  const u32x4 *xp = a.Xp + xlane;
+  const int NC = a.KT / D, c0 = (w * NC) / NW, c1 = ((w + 1) * NC) / NW;
+
+  f32x4 acc[NACC];
+#pragma unroll
+  for (int i = 0; i < NACC; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  u32x4 xb[D][2], wb[D][NACC];
+  if (c0 < c1) {
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+      const size_t t = (size_t)c0 * D + j;
+      xb[j][0] = xp[t * 128];
+      xb[j][1] = xp[t * 128 + 64];
+#pragma unroll
+      for (int i = 0; i < NACC; ++i) wb[j][i] = wp[t * kstride + i * 64];
+    }
+  }
+
+  // 1/rms of every row from the producer's partial sums of x^2 ([P_in][16] floats): wave 0
+  // sums them with wide independent loads while its weight loads are in flight and
+  // publishes the 16 values through LDS (read after the barrier below).  Fixed order.
+  __shared__ float rinv_s[16];
+  if (NORM && w == 0) {
+    const float4 *pp = reinterpret_cast<const float4 *>(a.ssq_in);
+    const int n4 = a.P_in * 4;   // float4 count; lane l covers rows 4*(l%4)..+3 of partial (i*64+l)/4
+    float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
+    for (int i = lane; i < n4; i += 64) {
+      const float4 v = pp[i];
+      t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
+    }
+#pragma unroll
+    for (int o = 4; o < 64; o <<= 1) {
+      t.x += __shfl_xor(t.x, o, 64); t.y += __shfl_xor(t.y, o, 64);
+      t.z += __shfl_xor(t.z, o, 64); t.w += __shfl_xor(t.w, o, 64);
+    }
+    if (lane < 4) {
+      const float kk = (float)(a.KT * 32);
+      rinv_s[lane * 4 + 0] = 1.0f / sqrtf(t.x / kk + a.eps);
+      rinv_s[lane * 4 + 1] = 1.0f / sqrtf(t.y / kk + a.eps);
+      rinv_s[lane * 4 + 2] = 1.0f / sqrtf(t.z / kk + a.eps);
+      rinv_s[lane * 4 + 3] = 1.0f / sqrtf(t.w / kk + a.eps);
+    }
+  }
+
+  for (int c = c0; c < c1; ++c) {
+    const int cn = min(c + 1, c1 - 1);   // the last chunk re-issues its own loads (ignored)
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+#pragma unroll
+      for (int i = 0; i < NACC; ++i) {
+        const bf16x8 wa = __builtin_bit_cast(bf16x8, wb[j][i]);
+        acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, __builtin_bit_cast(bf16x8, xb[j][0]), acc[i], 0, 0, 0);
+        acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, __builtin_bit_cast(bf16x8, xb[j][1]), acc[i], 0, 0, 0);
+      }
+      const size_t t = (size_t)cn * D + j;
+      xb[j][0] = xp[t * 128];
+      xb[j][1] = xp[t * 128 + 64];
+#pragma unroll
+      for (int i = 0; i < NACC; ++i) wb[j][i] = wp[t * kstride + i * 64];
+    }
+  }
+
+  // cross-wave (split-K) reduction through LDS, fixed order
+#pragma unroll
+  for (int i = 0; i < NACC; ++i) red[w][i][lane] = acc[i];
+  __syncthreads();
+  const float rinv = NORM ? rinv_s[xrow] : 1.f;
+
+  constexpr int STEP = EPI == EPI_SWIGLU ? 2 : 1;
+  for (int rb = w * STEP; rb < NACC; rb += NW * STEP) {
+    const int nb = nb0 + rb;
+    if (nb < (int)blockIdx.x * NACC) continue;   // slid-back duplicate of a neighbour's row-block
+    f32x4 s = red[0][rb][lane];
+#pragma unroll
+    for (int ww = 1; ww < NW; ++ww) s += red[ww][rb][lane];
+    if (EPI == EPI_SWIGLU) {
+      // fused matrix interleaves gate (even row-blocks) and up (odd): h = silu(gate) * up
+      f32x4 u = red[0][rb + 1][lane];
+#pragma unroll
+      for (int ww = 1; ww < NW; ++ww) u += red[ww][rb + 1][lane];
+      if (row_ok) {
+        const int n = (nb >> 1) * 16 + g * 4;
+        packed_store4(a.Xp_out, m, n, silu_dev(s[0] * rinv) * (u[0] * rinv), silu_dev(s[1] * rinv) * (u[1] * rinv),
+                      silu_dev(s[2] * rinv) * (u[2] * rinv), silu_dev(s[3] * rinv) * (u[3] * rinv));
+      }
+    } else {
+      int si = 0, nbs = nb;
+      if (nb >= a.seg[0].nb_end) { si = 1; nbs = nb - a.seg[0].nb_end; }
+      if (nb >= a.seg[1].nb_end) { si = 2; nbs = nb - a.seg[1].nb_end; }
+      const int n = nbs * 16 + g * 4;   // this lane holds columns n..n+3 of row m
+      float4 o = make_float4(s[0] * rinv, s[1] * rinv, s[2] * rinv, s[3] * rinv);
+      float ssq = 0.f;
+      if (row_ok) {
+        float *yp = a.seg[si].Y + (size_t)m * a.seg[si].ldy + n;
+        if (a.bias && si == 0) {
+          const float4 b = *reinterpret_cast<const float4 *>(a.bias + n);
+          o.x += b.x; o.y += b.y; o.z += b.z; o.w += b.w;
+        }
+        if (EPI == EPI_RESID) {
+          const float4 old = *reinterpret_cast<const float4 *>(yp);
+          o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w;
+        }
+        *reinterpret_cast<float4 *>(yp) = o;
+        if (a.Xp_out) {
+          ssq = o.x * o.x + o.y * o.y + o.z * o.z + o.w * o.w;
+          float4 gn = make_float4(1.f, 1.f, 1.f, 1.f);
+          if (a.gain_out) gn = *reinterpret_cast<const float4 *>(a.gain_out + n);
+          packed_store4(a.Xp_out, m, n, o.x * gn.x, o.y * gn.y, o.z * gn.z, o.w * gn.w);
+        }
+      }
+      if (a.ssq_out) {   // partial sum of x^2 over this row-block's 16 columns
+        ssq += __shfl_xor(ssq, 16, 64);
+        ssq += __shfl_xor(ssq, 32, 64);
+        if (g == 0) a.ssq_out[nb * 16 + m] = ssq;
+      }
+    }
+  }
+}
+
+template <int EPI, bool NORM, int NACC, int NW, int D>
+static void launch_cfg(const GemmArgs &a, hipStream_t s) {
+  const int grid = (a.NBtot + NACC - 1) / NACC;
+  gemm_mfma_kernel<EPI, NORM, NACC, NW, D><<<grid, NW * 64, 0, s>>>(a);
+}
+
+// Shape -> (row-blocks per workgroup, waves, ring depth), tuned on MI355X: wide matrices
+// amortise the activation loads over 8 row-blocks, narrow ones need every CU.
+template <int EPI, bool NORM>
+static void launch_shape(const GemmArgs &a, hipStream_t s) {
+  if (EPI == EPI_SWIGLU) {
+    if (a.NBtot >= 1024) launch_cfg<EPI, NORM, 8, 4, 4>(a, s);
+    else if (a.NBtot >= 512) launch_cfg<EPI, NORM, 4, 4, 4>(a, s);
+    else launch_cfg<EPI, NORM, 2, 4, 4>(a, s);
+  } else {
+    if (a.NBtot >= 1536) launch_cfg<EPI, NORM, 8, 4, 4>(a, s);
+    else if (a.NBtot >= 640) launch_cfg<EPI, NORM, 4, 4, 8>(a, s);
+    else if (a.NBtot >= 384) launch_cfg<EPI, NORM, 2, 4, 8>(a, s);
+    else launch_cfg<EPI, NORM, 1, 4, 8>(a, s);
+  }
+}
+
+void launch_gemm_mfma(const GemmLaunch &L, hipStream_t s) {
+  GemmArgs a{};
+  a.W = (const u32x4 *)L.W->tiled;
+  a.NBtot = L.W->N / 16;
+  a.KT = L.W->K / 32;
+  a.Xp = (const u32x4 *)L.Xp;
+  a.rows = L.rows;
+  a.row0 = L.row0;
+  a.ssq_in = L.ssq_in; a.P_in = L.P_in; a.eps = L.eps;
+  a.bias = L.bias;
+  a.Xp_out = (u32x4 *)L.Xp_out; a.gain_out = L.gain_out; a.ssq_out = L.ssq_out;
+  int end = 0;
+  for (int i = 0; i < 3; ++i) {
+    if (i < L.nseg) end += L.seg_N[i] / 16;
+    a.seg[i] = GemmSeg{i < L.nseg ? L.Y[i] : nullptr, i < L.nseg ? L.ldy[i] : 0, i < L.nseg ? end : 0x7fffffff};
+  }
+  const bool norm = L.ssq_in != nullptr;
+  if (L.epi == EPI_SWIGLU) {
+    if (norm) launch_shape<EPI_SWIGLU, true>(a, s); else launch_shape<EPI_SWIGLU, false>(a, s);
+  } else if (L.epi == EPI_RESID) {
+    launch_shape<EPI_RESID, false>(a, s);
+  } else {
+    if (norm) launch_shape<EPI_STORE, true>(a, s); else launch_shape<EPI_STORE, false>(a, s);
+  }
+}
+
+// ------------------------------------------------------------------ packed-form producers
+// Embedding rows -> float residual stream, packed(x * gain) and the full-row sum of x^2.
+__global__ __launch_bounds__(256) void embed_packed_kernel(const uint16_t *emb, const int32_t *ids, int d,
+                                                           const float *gain, float *x, u32x4 *Xp, float *ssq) {
+  __shared__ float red[4];
+  const int r = blockIdx.x;
+  const uint16_t *src = emb + (size_t)ids[r] * d;
+  float ss = 0.f;
+  for (int k0 = threadIdx.x * 4; k0 < d; k0 += 1024) {
+    const uint2 raw = *reinterpret_cast<const uint2 *>(src + k0);
+    const float v0 = __uint_as_float(raw.x << 16), v1 = __uint_as_float(raw.x & 0xffff0000u);
+    const float v2 = __uint_as_float(raw.y << 16), v3 = __uint_as_float(raw.y & 0xffff0000u);
+    *reinterpret_cast<float4 *>(x + (size_t)r * d + k0) = make_float4(v0, v1, v2, v3);
+    ss += v0 * v0 + v1 * v1 + v2 * v2 + v3 * v3;
+    const float4 gn = *reinterpret_cast<const float4 *>(gain + k0);
+    packed_store4(Xp, r, k0, v0 * gn.x, v1 * gn.y, v2 * gn.z, v3 * gn.w);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  if (threadIdx.x == 0) ssq[r] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+void launch_embed_packed(const void *emb, const int32_t *ids_dev, int rows, int d, const float *gain, float *x,
+                         void *Xp, float *ssq, hipStream_t s) {
+  embed_packed_kernel<<<rows, 256, 0, s>>>((const uint16_t *)emb, ids_dev, d, gain, x, (u32x4 *)Xp, ssq);
+}
+
+// float rows [rows][ld] (* gain) -> packed; one workgroup per row
+__global__ void pack_rows_kernel(const float *src, int ld, int K, const float *gain, u32x4 *Xp) {
+  const int r = blockIdx.x;
+  for (int k0 = threadIdx.x * 4; k0 < K; k0 += blockDim.x * 4) {
+    float4 v = *reinterpret_cast<const float4 *>(src + (size_t)r * ld + k0);
+    if (gain) {
+      const float4 gn = *reinterpret_cast<const float4 *>(gain + k0);
+      v.x *= gn.x; v.y *= gn.y; v.z *= gn.z; v.w *= gn.w;
+    }
+    packed_store4(Xp, r, k0, v.x, v.y, v.z, v.w);
+  }
+}
+
+void launch_pack_rows(const float *src, int ld, int rows, int K, const float *gain, void *Xp, hipStream_t s) {
+  pack_rows_kernel<<<rows, 256, 0, s>>>(src, ld, K, gain, (u32x4 *)Xp);
+}
+
+// draft head input [feature ; embedding of the following token] -> packed, K = 2d
+__global__ void draft_cat_packed_kernel(const float *feat, int feat_ld, const uint16_t *emb, const int32_t *next_ids,
+                                        int d, u32x4 *Xp) {
+  const int r = blockIdx.x;
+  const uint16_t *e = emb + (size_t)next_ids[r] * d;
+  for (int k0 = threadIdx.x * 4; k0 < d; k0 += blockDim.x * 4) {
+    const float4 f = *reinterpret_cast<const float4 *>(feat + (size_t)r * feat_ld + k0);
+    packed_store4(Xp, r, k0, f.x, f.y, f.z, f.w);
+    const uint2 raw = *reinterpret_cast<const uint2 *>(e + k0);
+    packed_store4(Xp, r, d + k0, __uint_as_float(raw.x << 16), __uint_as_float(raw.x & 0xffff0000u),
+                  __uint_as_float(raw.y << 16), __uint_as_float(raw.y & 0xffff0000u));
+  }
+}
+
+void launch_draft_cat_packed(const float *feat, int feat_ld, const void *emb, const int32_t *next_ids, int rows, int d,
+                             void *Xp, hipStream_t s) {
+  draft_cat_packed_kernel<<<rows, 256, 0, s>>>(feat, feat_ld, (const uint16_t *)emb, next_ids, d, (u32x4 *)Xp);
+}
+
+}  // namespace ae

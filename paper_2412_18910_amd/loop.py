@@ -1,0 +1,61 @@
+"""Host loop over ae_step (Algorithm 1) with the counters of the paper's Table 2."""
+import numpy as np
+
+
+class Counters:
+    """N_draft / N_target / N_waste, tokens, tau as defined for Table 2."""
+
+    def __init__(self):
+        self.n_draft = self.n_target = self.n_waste = self.tokens = 0
+        self.ks, self.accs = [], []
+
+    def add(self, k, n_accepted):
+        self.n_draft += k
+        self.n_target += 1
+        self.n_waste += k - n_accepted
+        self.tokens += n_accepted + 1
+        self.ks.append(k)
+        self.accs.append(n_accepted)
+
+    def summary(self):
+        nt = max(self.n_target, 1)
+        return {"N_draft": self.n_draft, "N_target": self.n_target, "N_waste": self.n_waste,
+                "tokens": self.tokens, "tau": self.tokens / nt, "mean_accepted": float(np.mean(self.accs)) if self.accs else 0.0,
+                "mean_k": float(np.mean(self.ks)) if self.ks else 0.0}
+
+
+def scripted_override(formal, pos, k, n_match, vocab):
+    """Override table that makes the first n_match draft tokens equal the formal
+    (autoregressive) sequence and the next one differ from it; the draft head still runs
+    all its forwards.  formal[pos] is the token the target will emit next."""
+    if k == 0:
+        return None
+    ov = -np.ones(k, np.int32)
+    a = min(n_match, k)
+    ov[:a] = formal[pos:pos + a]
+    if a < k:
+        ov[a] = (int(formal[pos + a]) + 1) % vocab
+    return ov
+
+
+def run_scripted(engine, formal, pos, n_steps, script, k_mode="ldlp", k_fixed=4, counters=None, check=True):
+    """n_steps iterations of Alg. 1 with scripted acceptance.  Returns (tokens emitted, new pos).
+    k_mode: 'ldlp' (Eq. 3), 'fixed', or 'oracle' (k = scripted acceptance length)."""
+    vocab = engine.cfg.vocab
+    emitted = 0
+    for r in range(n_steps):
+        if k_mode == "ldlp":
+            k, _ = engine.ldlp()
+        elif k_mode == "fixed":
+            k = k_fixed
+        else:
+            k = int(script[r])
+        ov = scripted_override(formal, pos, k, int(script[r]), vocab)
+        kk, na, toks = engine.step(k_force=k, override_ids=ov)
+        if check and not np.array_equal(toks, formal[pos:pos + na + 1]):
+            raise RuntimeError(f"speculative output left the autoregressive sequence at token {pos}")
+        pos += na + 1
+        emitted += na + 1
+        if counters is not None:
+            counters.add(kk, na)
+    return emitted, pos
