@@ -56,7 +56,7 @@ bool tileable(const Mat &m) { return m.N % 16 == 0 && m.K % 256 == 0; }
 
 // Allocate a fused k-major tiled matrix and fill it from up to three row-major sources.
 // stride 1: sources stacked ([q;k;v]); stride 2 (two sources): row-blocks interleaved (gate, up).
-int retile_fused(ae_ctx *c, Mat &dst, const Mat *const *src, int nsrc, bool interleave) {
+int retile_fused(ae_ctx *c, Mat &dst, const Mat *const *src, int nsrc, bool interleave, int rope_srcs = 0) {
   int N = 0;
   for (int i = 0; i < nsrc; ++i) N += src[i]->N;
   const int K = src[0]->K, NBtot = N / 16;
@@ -66,8 +66,9 @@ int retile_fused(ae_ctx *c, Mat &dst, const Mat *const *src, int nsrc, bool inte
   dst.tiled = p; dst.rowmajor = nullptr; dst.N = N; dst.K = K;
   int off = 0;
   for (int i = 0; i < nsrc; ++i) {
-    if (interleave) launch_retile(src[i]->rowmajor, src[i]->N, K, p, NBtot, i, nsrc, c->stream);
-    else launch_retile(src[i]->rowmajor, src[i]->N, K, p, NBtot, off, 1, c->stream);
+    const int perm = i < rope_srcs ? c->cfg.head_dim : 0;   // q / k rows in rotary-pair order
+    if (interleave) launch_retile(src[i]->rowmajor, src[i]->N, K, p, NBtot, i, nsrc, perm, c->stream);
+    else launch_retile(src[i]->rowmajor, src[i]->N, K, p, NBtot, off, 1, perm, c->stream);
     off += src[i]->N / 16;
   }
   return AE_OK;
@@ -90,12 +91,12 @@ void run_layer(ae_ctx *c, int li, float *x, int rows, int pos0, const float *nex
     const int Pd = d / 16;
     GemmLaunch qkv;
     qkv.W = &w.f_qkv; qkv.Xp = c->xp_a; qkv.rows = rows; qkv.ssq_in = c->ssq_a; qkv.P_in = c->Pa; qkv.eps = g.rms_eps;
-    qkv.epi = EPI_STORE; qkv.nseg = 3;
-    qkv.Y[0] = c->q; qkv.Y[1] = c->kbuf; qkv.Y[2] = c->vbuf;
-    qkv.ldy[0] = dq; qkv.ldy[1] = dkv; qkv.ldy[2] = dkv;
+    qkv.epi = EPI_QKV; qkv.nseg = 3;   // rotary embedding + KV append happen in the epilogue
+    qkv.Y[0] = c->q; qkv.ldy[0] = dq;
     qkv.seg_N[0] = dq; qkv.seg_N[1] = dkv; qkv.seg_N[2] = dkv;
+    qkv.rope_tab = c->rope_tab; qkv.Kc = kv_layer_ptr(c, li); qkv.Vc = (char *)kv_layer_ptr(c, li) + c->kv_v_offset;
+    qkv.pos0 = pos0; qkv.n_ctx = kv_capacity(g); qkv.hd = g.head_dim;
     launch_gemm_mfma(qkv, s);
-    launch_rope_append(c->q, c->kbuf, c->vbuf, rows, pos0, g, c->rope_tab, kv_layer_ptr(c, li), c->kv_v_offset, true, s);
     launch_attention_mfma(c->q, rows, pos0, g, kv_layer_ptr(c, li), c->kv_v_offset, c->attn_part, c->xp_att, s);
     GemmLaunch o;
     o.W = &w.wo; o.Xp = c->xp_att; o.rows = rows; o.epi = EPI_RESID; o.Y[0] = x; o.ldy[0] = d; o.seg_N[0] = d;
@@ -181,7 +182,8 @@ void draft_rows(ae_ctx *c, const float *feat, int feat_ld, const int32_t *next_i
   run_layer(c, g.n_layers, c->x, rows, slot0, nullptr);
 }
 
-// LM head (shared with the target) on draft-head output row `row` -> dlogits[i], argmax
+// LM head (shared with the target) on draft-head output row `row` -> dlogits[i], then the
+// head's token: argmax (greedy) or an inverse-CDF sample driven by u_draft[i] (temperature > 0)
 void draft_lm_head(ae_ctx *c, int row, int i) {
   const ae_config &g = c->cfg;
   float *dl = c->dlogits + (size_t)i * g.vocab;
@@ -193,7 +195,8 @@ void draft_lm_head(ae_ctx *c, int row, int i) {
   } else {
     gemm(c, c->lm_head, c->x + (size_t)row * g.d_model, g.d_model, 1, nullptr, dl, g.vocab, 0);
   }
-  launch_argmax(dl, 1, g.vocab, c->st->argmax, c->stream);
+  if (g.temperature > 0.f) launch_sample_draft(dl, g.vocab, g.temperature, c->st, i, c->prob, c->stream);
+  else launch_argmax(dl, 1, g.vocab, c->st->argmax, c->stream);
 }
 
 void enqueue_ldlp(ae_ctx *c, int slot, int f_row, bool relative_to_accept) {
@@ -264,7 +267,6 @@ int ae_init(const ae_config *cfg, const ae_weights *w, void *hip_stream, ae_ctx 
   if ((g.n_heads / g.n_kv_heads) * kMaxRows > 64)
     return fail(nullptr, AE_EUNSUPPORTED, "n_heads / n_kv_heads must be <= 4");
   if (g.n_ctx_max > kMaxSplits * kAttnChunk) return fail(nullptr, AE_EUNSUPPORTED, "n_ctx_max too large (<= 16384)");
-  if (g.temperature > 0.f) return fail(nullptr, AE_EUNSUPPORTED, "temperature > 0 is not implemented yet");
   if (!w->tok_emb || !w->final_norm || !w->lm_head || !w->layers || !w->draft_fc_w || !w->ldlp_w_in ||
       !w->ldlp_b_in || !w->ldlp_w_out || !w->ldlp_b_out || (g.ldlp_n_res > 0 && (!w->ldlp_w_res || !w->ldlp_b_res)))
     return fail(nullptr, AE_EINVAL, "ae_init: NULL weight pointer");
@@ -322,7 +324,7 @@ int ae_init(const ae_config *cfg, const ae_weights *w, void *hip_stream, ae_ctx 
       const Mat *qkv[3] = {&l.wq, &l.wk, &l.wv};
       const Mat *gu[2] = {&l.w_gate, &l.w_up};
       Mat t;
-      if ((rc = retile_fused(c, l.f_qkv, qkv, 3, false)) || (rc = retile_fused(c, l.f_gu, gu, 2, true))) return bail(rc);
+      if ((rc = retile_fused(c, l.f_qkv, qkv, 3, false, 2)) || (rc = retile_fused(c, l.f_gu, gu, 2, true))) return bail(rc);
       one[0] = &l.wo; t = l.wo;
       if ((rc = retile_fused(c, t, one, 1, false))) return bail(rc);
       l.wo.tiled = t.tiled;
@@ -370,7 +372,8 @@ int ae_init(const ae_config *cfg, const ae_weights *w, void *hip_stream, ae_ctx 
       (rc = dev_alloc(c, &c->dlogits, (size_t)(g.k_max > 0 ? g.k_max : 1) * V)) ||
       (rc = dev_alloc(c, &c->attn_part, attn_part_floats(g))) || (rc = dev_alloc(c, &c->ldlp_u, (size_t)2 * d)) ||
       (rc = dev_alloc(c, &c->ldlp_z, (size_t)kMaxLdlpHidden)) ||
-      (rc = dev_alloc(c, &c->hist, (size_t)g.n_ctx_max + 2)) || (rc = dev_alloc(c, &c->st, 1)))
+      (rc = dev_alloc(c, &c->hist, (size_t)g.n_ctx_max + 2)) || (rc = dev_alloc(c, &c->st, 1)) ||
+      (rc = dev_alloc(c, &c->prob, (size_t)4 * kMaxRows + 4)))
     return bail(rc);
   launch_rope_table(c->rope_tab, g.n_ctx_max, g.head_dim, g.rope_base, c->stream);
   launch_fill_zero(c->st, (sizeof(DevState) + 15) / 16 * 16, c->stream);
@@ -498,12 +501,19 @@ int ae_draft(ae_ctx *c, int k, const int32_t *override_ids, const double *u_draf
   if (override_ids)
     for (int i = 0; i < k; ++i)
       if (override_ids[i] >= g.vocab) return fail(c, AE_EINVAL, "ae_draft: override id out of range");
-  (void)u_draft;
+  if (g.temperature > 0.f && k > 0 && !u_draft) return fail(c, AE_EINVAL, "ae_draft: temperature > 0 needs u_draft");
   hipStream_t s = c->stream;
-  // upload the override table (-1 = keep the head's own token)
+  // upload the override table (-1 = keep the head's own token) and the sampling uniforms
   DevState *up = (DevState *)c->h_ids;
   for (int i = 0; i < kMaxRows; ++i) up->override_ids[i] = (override_ids && i < k) ? override_ids[i] : -1;
   HIPCHK(c, hipMemcpyAsync(c->st->override_ids, up->override_ids, sizeof(up->override_ids), hipMemcpyHostToDevice, s));
+  if (g.temperature > 0.f && k > 0) {
+    for (int i = 0; i < k; ++i) {
+      if (!(u_draft[i] >= 0.0 && u_draft[i] < 1.0)) return fail(c, AE_EINVAL, "ae_draft: u_draft outside [0,1)");
+      up->u_draft[i] = u_draft[i];
+    }
+    HIPCHK(c, hipMemcpyAsync(c->st->u_draft, up->u_draft, sizeof(double) * k, hipMemcpyHostToDevice, s));
+  }
   // catch-up over the slots validated by the last accept: true feature + following token
   draft_rows(c, c->F + (size_t)(c->nF - catch_rows) * g.d_model, g.d_model, c->hist + c->dlen + 1, catch_rows, c->dlen);
   c->dlen = n;
@@ -556,9 +566,21 @@ int ae_verify(ae_ctx *c, const int32_t *block_ids, int rows) {
 int ae_accept(ae_ctx *c, const double *u, int *n_accepted, int32_t *bonus) {
   if (!c) return AE_EINVAL;
   if (!c->have_verify) return fail(c, AE_ESTATE, "ae_accept: nothing verified");
-  (void)u;
+  const ae_config &g = c->cfg;
   const int n = c->kv_len, rows = c->block_rows;
-  launch_accept_greedy(c->st, c->hist, n, rows, c->stream);
+  if (g.temperature > 0.f) {
+    if (!u) return fail(c, AE_EINVAL, "ae_accept: temperature > 0 needs the uniforms u");
+    if (rows > 1 && !c->have_draft) return fail(c, AE_ESTATE, "ae_accept: rejection sampling needs the draft's own logits");
+    DevState *up = (DevState *)c->h_ids;
+    for (int i = 0; i < rows; ++i) {
+      if (!(u[i] >= 0.0 && u[i] < 1.0)) return fail(c, AE_EINVAL, "ae_accept: u outside [0,1)");
+      up->u_accept[i] = u[i];
+    }
+    HIPCHK(c, hipMemcpyAsync(c->st->u_accept, up->u_accept, sizeof(double) * rows, hipMemcpyHostToDevice, c->stream));
+    launch_accept_sample(c->logits, c->dlogits, g.vocab, rows - 1, g.temperature, c->st, c->hist, n, c->prob, c->stream);
+  } else {
+    launch_accept_greedy(c->st, c->hist, n, rows, c->stream);
+  }
   // Alg. 1 predicts the next draft length right after the verification
   const bool spec = c->have_draft;
   if (spec) enqueue_ldlp(c, n, 0, true);

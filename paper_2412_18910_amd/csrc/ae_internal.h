@@ -159,8 +159,9 @@ void launch_accept_sample(const float *tl, const float *dl, int V, int k, float 
 // ---- bf16 MFMA path (kernels_mfma.hip) ----
 // Row-block nb of a row-major [N,K] matrix -> row-block nb_off + nb*nb_stride of a fused
 // k-major tiled matrix with NBtot row-blocks.
-void launch_retile(const void *rowmajor, int N, int K, void *tiled, int NBtot, int nb_off, int nb_stride, hipStream_t s);
-enum { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
+void launch_retile(const void *rowmajor, int N, int K, void *tiled, int NBtot, int nb_off, int nb_stride, int perm_hd,
+                   hipStream_t s);
+enum { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_QKV = 3 };
 struct GemmLaunch {
   const Mat *W = nullptr;         // fused tiled matrix: N = all output rows, K
   const void *Xp = nullptr;       // packed activations
@@ -177,6 +178,10 @@ struct GemmLaunch {
   void *Xp_out = nullptr;         // packed output for the next GEMM
   const float *gain_out = nullptr;
   float *ssq_out = nullptr;
+  // EPI_QKV: rotary embedding + KV append fused into the epilogue
+  const float2 *rope_tab = nullptr;
+  void *Kc = nullptr, *Vc = nullptr;
+  int pos0 = 0, n_ctx = 0, hd = 0;
 };
 void launch_gemm_mfma(const GemmLaunch &L, hipStream_t s);
 void launch_embed_packed(const void *emb, const int32_t *ids_dev, int rows, int d, const float *gain, float *x,

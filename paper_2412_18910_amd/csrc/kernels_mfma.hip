@@ -32,21 +32,31 @@ namespace ae {
 
 // ------------------------------------------------------------------ re-tiling (set-up)
 // Row-block nb of a row-major [N,K] bf16 matrix goes to row-block (nb_off + nb*nb_stride)
-// of a fused k-major tiled matrix with NBtot row-blocks.
-__global__ void retile_kernel(const uint4 *src, uint4 *dst, int NB, int KT, int NBtot, int nb_off, int nb_stride) {
+// of a fused k-major tiled matrix with NBtot row-blocks.  perm_hd != 0 (q and k
+// projections, perm_hd = head_dim) reorders the rows of every head so that tile j of a head
+// holds rows 8j..8j+7 followed by their rotary partners hd/2+8j..hd/2+8j+7: a rotary
+// pair then sits in lanes l and l^32 of the same accumulator (see the EPI_QKV epilogue).
+__global__ void retile_kernel(const uint4 *src, uint4 *dst, int NB, int KT, int NBtot, int nb_off, int nb_stride,
+                              int perm_hd) {
   const size_t total = (size_t)NB * KT * 64;
   for (size_t o = blockIdx.x * (size_t)blockDim.x + threadIdx.x; o < total; o += (size_t)gridDim.x * blockDim.x) {
     const int lane = o & 63;
     const size_t tile = o >> 6;
     const int nb = tile % NB;
     const size_t kt = tile / NB;
-    const size_t row = (size_t)nb * 16 + (lane & 15);
+    size_t row = (size_t)nb * 16 + (lane & 15);
+    if (perm_hd) {
+      const int bph = perm_hd / 16, head = nb / bph, j = nb % bph, rho = lane & 15;
+      row = (size_t)head * perm_hd + (rho < 8 ? 8 * j + rho : perm_hd / 2 + 8 * j + rho - 8);
+    }
     dst[(kt * NBtot + nb_off + (size_t)nb * nb_stride) * 64 + lane] = src[row * (size_t)(KT * 4) + kt * 4 + (lane >> 4)];
   }
 }
 
-void launch_retile(const void *rowmajor, int N, int K, void *tiled, int NBtot, int nb_off, int nb_stride, hipStream_t s) {
-  retile_kernel<<<2048, 256, 0, s>>>((const uint4 *)rowmajor, (uint4 *)tiled, N / 16, K / 32, NBtot, nb_off, nb_stride);
+void launch_retile(const void *rowmajor, int N, int K, void *tiled, int NBtot, int nb_off, int nb_stride, int perm_hd,
+                   hipStream_t s) {
+  retile_kernel<<<2048, 256, 0, s>>>((const uint4 *)rowmajor, (uint4 *)tiled, N / 16, K / 32, NBtot, nb_off, nb_stride,
+                                     perm_hd);
 }
 
 // ------------------------------------------------------------------ GEMM
@@ -69,7 +79,18 @@ struct GemmArgs {
   GemmSeg seg[3];
   int NBtot, KT, rows, row0, P_in;   // output row m reads packed row row0 + m
   float eps;
+  // EPI_QKV: rotary embedding + KV-cache append in the epilogue
+  const float2 *rope_tab;   // [slot][hd/2] (cos, sin)
+  uint16_t *Kc, *Vc;        // this layer's tiled bf16 cache (layouts of kernels_attn_mfma.hip)
+  int pos0, n_ctx, hd;
 };
+
+__device__ __forceinline__ uint16_t f2bf_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7f800000u) == 0x7f800000u) return (uint16_t)(u >> 16);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
 
 template <int EPI, bool NORM, int NACC, int NW, int D>
 __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(const GemmArgs a) {
@@ -171,6 +192,50 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(const GemmArgs a) {
         packed_store4(a.Xp_out, m, n, silu_dev(s[0] * rinv) * (u[0] * rinv), silu_dev(s[1] * rinv) * (u[1] * rinv),
                       silu_dev(s[2] * rinv) * (u[2] * rinv), silu_dev(s[3] * rinv) * (u[3] * rinv));
       }
+    } else if (EPI == EPI_QKV) {
+      // Row-blocks [0, seg0) = q, [seg0, seg1) = k (both with the rotary row order of
+      // retile_kernel), [seg1, ..) = v.  q: rotate, store float in natural column order.
+      // k: rotate, round to bf16, append to the tiled K cache.  v: round, append.
+      int si = 0, nbs = nb;
+      if (nb >= a.seg[0].nb_end) { si = 1; nbs = nb - a.seg[0].nb_end; }
+      if (nb >= a.seg[1].nb_end) { si = 2; nbs = nb - a.seg[1].nb_end; }
+      const int hd = a.hd, bph = hd >> 4, head = nbs / bph, j = nbs % bph;
+      const int slot = a.pos0 + (row_ok ? m : 0);
+      float4 o = make_float4(s[0] * rinv, s[1] * rinv, s[2] * rinv, s[3] * rinv);
+      if (si < 2) {
+        const int i0 = 8 * j + 4 * (g & 1);   // rotary index of the pair, first-half coordinates
+        const float4 cs01 = *reinterpret_cast<const float4 *>(a.rope_tab + (size_t)slot * (hd >> 1) + i0);
+        const float4 cs23 = *reinterpret_cast<const float4 *>(a.rope_tab + (size_t)slot * (hd >> 1) + i0 + 2);
+        const float sgn = g < 2 ? -1.f : 1.f;   // first half: a*c - b*s; second half: b*c + a*s
+        const float p0 = __shfl_xor(o.x, 32, 64), p1 = __shfl_xor(o.y, 32, 64);
+        const float p2 = __shfl_xor(o.z, 32, 64), p3 = __shfl_xor(o.w, 32, 64);
+        o.x = o.x * cs01.x + sgn * p0 * cs01.y;
+        o.y = o.y * cs01.z + sgn * p1 * cs01.w;
+        o.z = o.z * cs23.x + sgn * p2 * cs23.y;
+        o.w = o.w * cs23.z + sgn * p3 * cs23.w;
+        const int dcol = (g < 2 ? 0 : hd >> 1) + i0;   // natural head-dim index of o.x
+        if (row_ok) {
+          if (si == 0) {
+            *reinterpret_cast<float4 *>(a.seg[0].Y + (size_t)m * a.seg[0].ldy + head * hd + dcol) = o;
+          } else {
+            // K tile layout: [kh][slot/16][d/32][lane = ((d%32)/8)*16 + slot%16][d%8]
+            const size_t idx = ((((size_t)head * (a.n_ctx >> 4) + (slot >> 4)) * (hd >> 5) + (dcol >> 5)) * 64 +
+                                ((dcol & 31) >> 3) * 16 + (slot & 15)) * 8 + (dcol & 7);
+            u32x2 pk;
+            pk[0] = (uint32_t)f2bf_rne(o.x) | ((uint32_t)f2bf_rne(o.y) << 16);
+            pk[1] = (uint32_t)f2bf_rne(o.z) | ((uint32_t)f2bf_rne(o.w) << 16);
+            *reinterpret_cast<u32x2 *>(a.Kc + idx) = pk;
+          }
+        }
+      } else if (row_ok) {
+        // V tile layout: [kh][slot/32][d/16][lane = ((slot%16)/4)*16 + d%16][e = slot%4 + 4*((slot%32)/16)]
+        const int w16 = slot & 15, e = (w16 & 3) + 4 * ((slot & 31) >> 4);
+        const size_t base = ((((size_t)head * (a.n_ctx >> 5) + (slot >> 5)) * bph + j) * 64 + (w16 >> 2) * 16 + g * 4) * 8 + e;
+        a.Vc[base] = f2bf_rne(o.x);
+        a.Vc[base + 8] = f2bf_rne(o.y);
+        a.Vc[base + 16] = f2bf_rne(o.z);
+        a.Vc[base + 24] = f2bf_rne(o.w);
+      }
     } else {
       int si = 0, nbs = nb;
       if (nb >= a.seg[0].nb_end) { si = 1; nbs = nb - a.seg[0].nb_end; }
@@ -223,7 +288,7 @@ static void launch_shape(const GemmArgs &a, hipStream_t s) {
     if (a.NBtot >= 1536) launch_cfg<EPI, NORM, 8, 4, 4>(a, s);
     else if (a.NBtot >= 640) launch_cfg<EPI, NORM, 4, 4, 8>(a, s);
     else if (a.NBtot >= 384) launch_cfg<EPI, NORM, 2, 4, 8>(a, s);
-    else launch_cfg<EPI, NORM, 1, 4, 8>(a, s);
+    else launch_cfg<EPI, NORM, 1, 4, 4>(a, s);   // narrow: (1,4,8), (1,8,*), (1,16,4), (2,8,8) measured no better
   }
 }
 
@@ -244,7 +309,11 @@ void launch_gemm_mfma(const GemmLaunch &L, hipStream_t s) {
     a.seg[i] = GemmSeg{i < L.nseg ? L.Y[i] : nullptr, i < L.nseg ? L.ldy[i] : 0, i < L.nseg ? end : 0x7fffffff};
   }
   const bool norm = L.ssq_in != nullptr;
-  if (L.epi == EPI_SWIGLU) {
+  a.rope_tab = L.rope_tab; a.Kc = (uint16_t *)L.Kc; a.Vc = (uint16_t *)L.Vc;
+  a.pos0 = L.pos0; a.n_ctx = L.n_ctx; a.hd = L.hd;
+  if (L.epi == EPI_QKV) {
+    launch_shape<EPI_QKV, true>(a, s);
+  } else if (L.epi == EPI_SWIGLU) {
     if (norm) launch_shape<EPI_SWIGLU, true>(a, s); else launch_shape<EPI_SWIGLU, false>(a, s);
   } else if (L.epi == EPI_RESID) {
     launch_shape<EPI_RESID, false>(a, s);

@@ -240,3 +240,79 @@ def test_edge_cases_and_errors():
         eng.draft(2)
     assert e.value.code == AE_ESTATE
     eng.close()
+
+
+def test_tiny_fp32_sampling_steps_match_oracle():
+    """temperature > 0: same uniforms on both sides => same sampled drafts, accepted lengths,
+    resampled / bonus tokens (float32 model: logits agree to ~1e-6, so no draw sits on an edge)."""
+    cfg = TINY.with_(temperature=0.8)
+    eng, orc, _ = make_pair(cfg, 8)
+    ids = synth.token_ids(48, cfg.vocab, 81)
+    orc.prefill(ids)
+    eng.prefill(ids)
+    assert eng.pending == orc.pending
+    accepted = 0
+    for r in range(24):
+        k = orc.ldlp()[0] if r % 3 else (r // 3) % (cfg.k_max + 1)
+        ud, ua = synth.uniforms(cfg.k_max, 1000 + r), synth.uniforms(cfg.k_max + 1, 2000 + r)
+        ko, nao, to = orc.step(k_force=k, u_draft=ud, u_accept=ua)
+        kg, nag, tg = eng.step(k_force=k, u_draft=ud, u_accept=ua)
+        assert (ko, nao) == (kg, nag) and np.array_equal(to, tg), r
+        accepted += nao
+    assert eng.kv_len == orc.kv_len
+    eng.close()
+
+
+def test_bf16_sampling_kernels_match_oracle_rule_on_gpu_logits():
+    """Accept-kernel parity: the oracle's rule applied to the logits the GPU produced must give
+    the GPU's own (n_accepted, bonus) and draft samples, for the same uniforms."""
+    import ctypes as C
+    from oracle import binding as ob
+    from .helpers import dp, fp, ip
+    cfg = SMALL_BF16.with_(temperature=1.0)
+    eng, orc, _ = make_pair(cfg, 9)
+    lib = ob.load()
+    ids = synth.token_ids(40, cfg.vocab, 91)
+    eng.prefill(ids)
+    V, T = cfg.vocab, float(cfg.temperature)
+    n_acc_hist = []
+    for r in range(16):
+        k = 1 + r % cfg.k_max
+        ud, ua = synth.uniforms(cfg.k_max, 3000 + r), synth.uniforms(cfg.k_max + 1, 4000 + r)
+        d = eng.draft(k, u_draft=ud)
+        dl = np.stack([eng.draft_logits(i) for i in range(k)])
+        for i in range(k):   # the sampled draft token is the inverse CDF of softmax(draft logits / T)
+            p = np.exp((dl[i].astype(np.float64) - dl[i].max()) / T)
+            assert lib.orc_sample_inverse_cdf(dp(np.ascontiguousarray(p)), V, float(ud[i])) == d[i], (r, i)
+        eng.verify(n_rows=k + 1)
+        tl = np.stack([eng.logits(i) for i in range(k + 1)])
+        na, b = C.c_int(), C.c_int32()
+        dd = np.ascontiguousarray(d, np.int32)
+        uu = np.ascontiguousarray(ua[:k + 1], np.float64)
+        lib.orc_accept_sample(fp(np.ascontiguousarray(tl)), fp(np.ascontiguousarray(dl)), V, k, ip(dd), T, dp(uu),
+                              C.byref(na), C.byref(b))
+        got = eng.accept(ua[:k + 1])
+        assert got == (na.value, b.value), r
+        n_acc_hist.append(got[0])
+    assert eng.kv_len == 40 + sum(n_acc_hist) + len(n_acc_hist)
+    eng.close()
+
+
+def test_sampling_argument_errors():
+    cfg = TINY.with_(temperature=0.5)
+    eng, _, _ = make_pair(cfg, 10)
+    eng.prefill(synth.token_ids(8, cfg.vocab, 3))
+    with pytest.raises(AdaEagleError) as e:
+        eng.draft(2)                                   # uniforms missing
+    assert e.value.code == AE_EINVAL
+    eng.draft(2, u_draft=[0.1, 0.7])
+    eng.verify(n_rows=3)
+    with pytest.raises(AdaEagleError) as e:
+        eng.accept()                                   # uniforms missing
+    assert e.value.code == AE_EINVAL
+    with pytest.raises(AdaEagleError) as e:
+        eng.accept([0.1, 1.0, 0.2])                    # 1.0 is outside [0, 1)
+    assert e.value.code == AE_EINVAL
+    na, b = eng.accept([0.1, 0.2, 0.3])
+    assert 0 <= na <= 2 and 0 <= b < cfg.vocab
+    eng.close()
