@@ -146,8 +146,9 @@ void target_forward(ae_ctx *c, const int32_t *ids_dev, int rows, int pos0, int l
       GemmLaunch lm;   // final RMSNorm folded into the LM head
       lm.W = &c->lm_head; lm.Xp = c->xp_a; lm.rows = nr; lm.row0 = logit_from; lm.ssq_in = c->ssq_a; lm.P_in = c->Pa;
       lm.eps = g.rms_eps; lm.epi = EPI_STORE; lm.Y[0] = c->logits; lm.ldy[0] = g.vocab; lm.seg_N[0] = g.vocab;
+      lm.amax_val = c->amax_val; lm.amax_idx = c->amax_idx;   // per-row argmax rides on the epilogue
       launch_gemm_mfma(lm, s);
-      launch_argmax(c->logits, nr, g.vocab, c->st->argmax, s);
+      launch_argmax_finish(c->amax_val, c->amax_idx, g.vocab / 16, nr, c->st, -1, s);
     }
     return;
   }
@@ -183,20 +184,29 @@ void draft_rows(ae_ctx *c, const float *feat, int feat_ld, const int32_t *next_i
 }
 
 // LM head (shared with the target) on draft-head output row `row` -> dlogits[i], then the
-// head's token: argmax (greedy) or an inverse-CDF sample driven by u_draft[i] (temperature > 0)
+// head's token i: argmax (greedy) or an inverse-CDF sample driven by u_draft[i] (temperature
+// > 0); the caller's override table is applied last.
 void draft_lm_head(ae_ctx *c, int row, int i) {
   const ae_config &g = c->cfg;
+  hipStream_t s = c->stream;
   float *dl = c->dlogits + (size_t)i * g.vocab;
+  const bool greedy = !(g.temperature > 0.f);
   if (c->fast) {
     GemmLaunch lm;
     lm.W = &c->lm_head; lm.Xp = c->xp_a; lm.rows = 1; lm.row0 = row; lm.epi = EPI_STORE;
     lm.Y[0] = dl; lm.ldy[0] = g.vocab; lm.seg_N[0] = g.vocab;
-    launch_gemm_mfma(lm, c->stream);
+    if (greedy) { lm.amax_val = c->amax_val; lm.amax_idx = c->amax_idx; }
+    launch_gemm_mfma(lm, s);
+    if (greedy) {
+      launch_argmax_finish(c->amax_val, c->amax_idx, g.vocab / 16, 1, c->st, i, s);   // argmax + override
+      return;
+    }
   } else {
     gemm(c, c->lm_head, c->x + (size_t)row * g.d_model, g.d_model, 1, nullptr, dl, g.vocab, 0);
   }
-  if (g.temperature > 0.f) launch_sample_draft(dl, g.vocab, g.temperature, c->st, i, c->prob, c->stream);
-  else launch_argmax(dl, 1, g.vocab, c->st->argmax, c->stream);
+  if (greedy) launch_argmax(dl, 1, g.vocab, c->st->argmax, s);
+  else launch_sample_draft(dl, g.vocab, g.temperature, c->st, i, c->prob, s);
+  launch_pick_draft(c->st, i, nullptr, s);
 }
 
 void enqueue_ldlp(ae_ctx *c, int slot, int f_row, bool relative_to_accept) {
@@ -338,7 +348,8 @@ int ae_init(const ae_config *cfg, const ae_weights *w, void *hip_stream, ae_ctx 
     if ((rc = dev_alloc(c, &pa, (size_t)g.d_model * 64)) || (rc = dev_alloc(c, &pf, (size_t)g.d_model * 64)) ||
         (rc = dev_alloc(c, &pt, dqq * 64)) || (rc = dev_alloc(c, &ph, (size_t)g.d_ffn * 64)) ||
         (rc = dev_alloc(c, &pc, (size_t)2 * g.d_model * 64)) ||
-        (rc = dev_alloc(c, &c->ssq_a, (size_t)g.d_model)) || (rc = dev_alloc(c, &c->ssq_f, (size_t)g.d_model)))
+        (rc = dev_alloc(c, &c->ssq_a, (size_t)g.d_model)) || (rc = dev_alloc(c, &c->ssq_f, (size_t)g.d_model)) ||
+        (rc = dev_alloc(c, &c->amax_val, (size_t)g.vocab)) || (rc = dev_alloc(c, &c->amax_idx, (size_t)g.vocab)))
       return bail(rc);
     c->xp_a = pa; c->xp_f = pf; c->xp_att = pt; c->xp_h = ph; c->xp_cat = pc;
     launch_fill_zero(pa, (size_t)g.d_model * 64, c->stream);
@@ -526,7 +537,6 @@ int ae_draft(ae_ctx *c, int k, const int32_t *override_ids, const double *u_draf
       fh_row = 0;
     }
     draft_lm_head(c, fh_row, i);
-    launch_pick_draft(c->st, i, nullptr, s);
   }
   c->cur_k = k;
   c->have_draft = true;

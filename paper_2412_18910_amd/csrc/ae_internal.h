@@ -81,6 +81,8 @@ struct ae_ctx {
   // bf16 fast path: packed activations (GEMM B operands) and RMSNorm partial sums
   void *xp_a = nullptr, *xp_f = nullptr, *xp_att = nullptr, *xp_h = nullptr, *xp_cat = nullptr;
   float *ssq_a = nullptr, *ssq_f = nullptr;
+  float *amax_val = nullptr;       // LM-head argmax partials [vocab/16][16]
+  int32_t *amax_idx = nullptr;
   int Pa = 0;                      // number of valid partial-sum rows in ssq_a
   double *prob = nullptr;          // T>0 scratch [2][V]
   int32_t *hist = nullptr;         // device token history by slot
@@ -178,12 +180,15 @@ struct GemmLaunch {
   void *Xp_out = nullptr;         // packed output for the next GEMM
   const float *gain_out = nullptr;
   float *ssq_out = nullptr;
+  float *amax_val = nullptr;      // LM head: per row-block argmax partials [N/16][16]
+  int32_t *amax_idx = nullptr;
   // EPI_QKV: rotary embedding + KV append fused into the epilogue
   const float2 *rope_tab = nullptr;
   void *Kc = nullptr, *Vc = nullptr;
   int pos0 = 0, n_ctx = 0, hd = 0;
 };
 void launch_gemm_mfma(const GemmLaunch &L, hipStream_t s);
+void launch_argmax_finish(const float *val, const int32_t *idx, int NB, int rows, DevState *st, int pick_i, hipStream_t s);
 void launch_embed_packed(const void *emb, const int32_t *ids_dev, int rows, int d, const float *gain, float *x,
                          void *Xp, float *ssq, hipStream_t s);
 void launch_pack_rows(const float *src, int ld, int rows, int K, const float *gain, void *Xp, hipStream_t s);

@@ -79,6 +79,8 @@ struct GemmArgs {
   GemmSeg seg[3];
   int NBtot, KT, rows, row0, P_in;   // output row m reads packed row row0 + m
   float eps;
+  float *amax_val;      // EPI_STORE, LM head: per row-block, per row maximum of the outputs ...
+  int32_t *amax_idx;    // ... and the lowest column index attaining it ([NBtot][16] each)
   // EPI_QKV: rotary embedding + KV-cache append in the epilogue
   const float2 *rope_tab;   // [slot][hd/2] (cos, sin)
   uint16_t *Kc, *Vc;        // this layer's tiled bf16 cache (layouts of kernels_attn_mfma.hip)
@@ -254,6 +256,15 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(const GemmArgs a) {
           o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w;
         }
         *reinterpret_cast<float4 *>(yp) = o;
+        if (EPI == EPI_STORE && a.amax_val) {
+          // argmax partial of this row-block: columns ascend with (g, component), ties keep the lowest
+          float bv = o.x; int bi = n;
+          if (o.y > bv) { bv = o.y; bi = n + 1; }
+          if (o.z > bv) { bv = o.z; bi = n + 2; }
+          if (o.w > bv) { bv = o.w; bi = n + 3; }
+          ssq = bv;               // reuse the two registers for the cross-lane step below
+          nbs = bi;
+        }
         if (a.Xp_out) {
           ssq = o.x * o.x + o.y * o.y + o.z * o.z + o.w * o.w;
           float4 gn = make_float4(1.f, 1.f, 1.f, 1.f);
@@ -261,7 +272,17 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(const GemmArgs a) {
           packed_store4(a.Xp_out, m, n, o.x * gn.x, o.y * gn.y, o.z * gn.z, o.w * gn.w);
         }
       }
-      if (a.ssq_out) {   // partial sum of x^2 over this row-block's 16 columns
+      if (EPI == EPI_STORE && a.amax_val) {
+        float bv = row_ok ? ssq : -INFINITY;
+        int bi = row_ok ? nbs : 0x7fffffff;
+#pragma unroll
+        for (int o2 = 16; o2 < 64; o2 <<= 1) {
+          const float ov = __shfl_xor(bv, o2, 64);
+          const int oi = __shfl_xor(bi, o2, 64);
+          if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+        }
+        if (g == 0) { a.amax_val[nb * 16 + m] = bv; a.amax_idx[nb * 16 + m] = bi; }
+      } else if (a.ssq_out) {   // partial sum of x^2 over this row-block's 16 columns
         ssq += __shfl_xor(ssq, 16, 64);
         ssq += __shfl_xor(ssq, 32, 64);
         if (g == 0) a.ssq_out[nb * 16 + m] = ssq;
@@ -309,6 +330,7 @@ void launch_gemm_mfma(const GemmLaunch &L, hipStream_t s) {
     a.seg[i] = GemmSeg{i < L.nseg ? L.Y[i] : nullptr, i < L.nseg ? L.ldy[i] : 0, i < L.nseg ? end : 0x7fffffff};
   }
   const bool norm = L.ssq_in != nullptr;
+  a.amax_val = L.amax_val; a.amax_idx = L.amax_idx;
   a.rope_tab = L.rope_tab; a.Kc = (uint16_t *)L.Kc; a.Vc = (uint16_t *)L.Vc;
   a.pos0 = L.pos0; a.n_ctx = L.n_ctx; a.hd = L.hd;
   if (L.epi == EPI_QKV) {
@@ -320,6 +342,45 @@ void launch_gemm_mfma(const GemmLaunch &L, hipStream_t s) {
   } else {
     if (norm) launch_shape<EPI_STORE, true>(a, s); else launch_shape<EPI_STORE, false>(a, s);
   }
+}
+
+// Final argmax over the LM head's row-block partials (lowest token id wins ties), one
+// workgroup per row.  pick_i >= 0 (draft head, one row): also applies the caller's override
+// table and records draft token pick_i.
+__global__ __launch_bounds__(256) void argmax_finish_kernel(const float *val, const int32_t *idx, int NB, DevState *st,
+                                                            int pick_i) {
+  __shared__ float bv[4];
+  __shared__ int bi[4];
+  const int row = blockIdx.x;
+  float best = -INFINITY;
+  int best_i = 0x7fffffff;
+  for (int p = threadIdx.x; p < NB; p += 256) {
+    const float v = val[p * 16 + row];
+    const int i = idx[p * 16 + row];
+    if (v > best || (v == best && i < best_i)) { best = v; best_i = i; }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float ov = __shfl_xor(best, o, 64);
+    const int oi = __shfl_xor(best_i, o, 64);
+    if (ov > best || (ov == best && oi < best_i)) { best = ov; best_i = oi; }
+  }
+  if ((threadIdx.x & 63) == 0) { bv[threadIdx.x >> 6] = best; bi[threadIdx.x >> 6] = best_i; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w)
+      if (bv[w] > best || (bv[w] == best && bi[w] < best_i)) { best = bv[w]; best_i = bi[w]; }
+    int32_t t = best_i == 0x7fffffff ? 0 : best_i;
+    st->argmax[row] = t;
+    if (pick_i >= 0) {
+      if (st->override_ids[pick_i] >= 0) t = st->override_ids[pick_i];
+      st->draft_ids[pick_i] = t;
+    }
+  }
+}
+
+void launch_argmax_finish(const float *val, const int32_t *idx, int NB, int rows, DevState *st, int pick_i, hipStream_t s) {
+  argmax_finish_kernel<<<rows, 256, 0, s>>>(val, idx, NB, st, pick_i);
 }
 
 // ------------------------------------------------------------------ packed-form producers
