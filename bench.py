@@ -29,6 +29,16 @@ def draft_bytes(cfg, n):
     return 2 * ((2 * d * dq + 2 * d * dkv + 3 * d * f) + 2 * d * d + V * d) + 2 * 2 * n * dkv
 
 
+def profiled_traffic():
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary."""
+    import re
+    try:
+        text = open(os.path.join(ROOT, "profiles", "adaeagle_step_7b_bf16.md")).read()
+        return int(re.search(r"TRAFFIC_BYTES_PER_LAUNCH[^=]*=\s*(\d+)", text).group(1))
+    except Exception:
+        return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -38,6 +48,8 @@ def main():
     ap.add_argument("--context", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run 4 plain device copies of 512 MiB (counter calibration under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (one sequence, one MI355X); --gpus must be 1",
@@ -156,9 +168,16 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "gemm_mfma_kernel<EPI_SWIGLU, norm> (fused RMSNorm + gate/up + SwiGLU)",
                      "achieved": round(achieved, 1), "peak": 8000.0, "unit": "GB/s", "frac": round(achieved / 8000.0, 4),
                      "bytes_per_launch": gate_up_bytes, "avg_launch_us": round(kern_us, 2), "launches": kt_n,
-                     "traffic": None},
+                     "traffic": profiled_traffic() if args.preset == "7b" else None},
         "paper_context": "paper: 66.35 tok/s AdaEAGLE vs 39.36 AR (1.62x) on A800 fp32, Vicuna-7B, MT-Bench",
     }
+
+    if args.calibrate_copy:
+        src = torch.empty(512 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        sync()
 
     # ---- CPU oracle on the host cores, bounded sample
     if not args.no_cpu_baseline:
