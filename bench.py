@@ -195,7 +195,7 @@ def cpu_baseline(cfg, w, synth):
     context (CPU time is weight-bound and insensitive to the context length)."""
     import numpy as np
     from oracle import binding as ob
-    n_ctx, n_steps, k = 64, 2, 4
+    n_ctx, n_steps, k = 64, 8, 4
     ocfg = cfg.with_(n_ctx_max=n_ctx + 64).dict()
     ocfg["wdtype"] = ocfg.pop("dtype")
     hw = synth.weights_to_numpy(w)

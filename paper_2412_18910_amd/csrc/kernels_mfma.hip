@@ -13,7 +13,7 @@
 //    which measured ~25% faster than strip-major storage on MI355X.
 //  * Activations travel between kernels already in B-operand form ("packed"): for every
 //    k-tile two 1 KB tiles (bf16 hi, bf16 lo; x ~= hi + lo keeps 16 significant bits),
-//    lane = (k-octet)*16 + row.  Producers (embedding, GEMM epilogues, attention merge)
+//    slot = row*4 + k-octet (rows contiguous).  Producers (embedding, GEMM epilogues, attention merge)
 //    write this form, so the GEMM hot loop is only loads and MFMAs (two per weight tile).
 //  * A workgroup owns NACC adjacent row-blocks and splits K over its NW waves; every wave
 //    runs a register ring of D k-tiles (loads for tile t+D are issued when tile t is
@@ -103,7 +103,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(const GemmArgs a) {
   const int nb0 = min((int)blockIdx.x * NACC, a.NBtot - NACC);
   const bool row_ok = m < a.rows;
   const int xrow = a.row0 + (row_ok ? m : a.rows - 1);    // rows beyond the block re-read the last row
-  const int xlane = g * 16 + xrow;
+  const int xlane = xrow * 4 + g;   // packed slot of (row, k-octet)
 
   const u32x4 *wp = a.W + (size_t)nb0 * 64 + lane;
   const size_t kstride = (size_t)a.NBtot * 64;

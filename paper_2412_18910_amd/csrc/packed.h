@@ -1,7 +1,9 @@
 // Shared device helpers of the bf16 MFMA path: vector typedefs, the bf16 hi/lo split and
 // the "packed" activation layout (B operand of v_mfma_f32_16x16x32_bf16):
-//   Xp[kt][h][lane] (16 bytes each), h = 0 hi / 1 lo, lane = ((k%32)/8)*16 + row,
-//   holding k = kt*32 + (lane/16)*8 .. +7 of that row.
+//   Xp[kt][h][slot] (16 bytes each), h = 0 hi / 1 lo, slot = row*4 + (k%32)/8, holding
+//   k = kt*32 + (slot%4)*8 .. +7 of that row.  MFMA lane (k-octet g, row m) reads slot m*4+g:
+//   the rows of a tile are contiguous (64 bytes each), so a block of r rows touches only
+//   ceil(r/2) cache lines per tile.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -32,8 +34,8 @@ __device__ __forceinline__ void packed_store4(u32x4 *Xp, int m, int k0, float a,
   split2(a, b, h0, l0);
   split2(c, d, h1, l1);
   const int kt = k0 >> 5, g = (k0 & 31) >> 3, half = (k0 & 7) >> 2;
-  u32x2 *ph = reinterpret_cast<u32x2 *>(Xp + ((size_t)kt * 2 + 0) * 64 + g * 16 + m) + half;
-  u32x2 *pl = reinterpret_cast<u32x2 *>(Xp + ((size_t)kt * 2 + 1) * 64 + g * 16 + m) + half;
+  u32x2 *ph = reinterpret_cast<u32x2 *>(Xp + ((size_t)kt * 2 + 0) * 64 + m * 4 + g) + half;
+  u32x2 *pl = reinterpret_cast<u32x2 *>(Xp + ((size_t)kt * 2 + 1) * 64 + m * 4 + g) + half;
   *ph = u32x2{h0, h1};
   *pl = u32x2{l0, l1};
 }
