@@ -392,3 +392,12 @@ def test_8b_gqa_shape_reduced_depth_step_matches_oracle():
     assert worst < 2e-2
     cfg = cfg.with_(temperature=1.0)
     _full_size_step(cfg, 3, 300, ks=[5], sampling=True)
+
+
+def test_13b_shape_reduced_depth_step_matches_oracle():
+    """13B width (d 5120, 40 heads, FFN 13824) at 2 layers with k_max = 10: 11-row verify blocks,
+    a 3000-slot cache (12 attention chunks) and the ragged-tail GEMM shapes of this model."""
+    from paper_2412_18910_amd.config import LLAMA_13B
+    cfg = LLAMA_13B.with_(n_layers=2, n_ctx_max=3000 + 64)
+    worst = _full_size_step(cfg, 4, 3000, ks=[10, 0, 6])
+    assert worst < 2e-2
