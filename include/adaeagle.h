@@ -61,6 +61,8 @@ typedef struct {
   int32_t ldlp_hidden;   /* width h of the LDLP hidden layers (<= 1024) */
   int32_t ldlp_n_res;    /* residual h->h blocks between input and output layer */
   float temperature;     /* 0: greedy (Sec. 3.1); > 0: rejection sampling (Sec. 2.1) */
+  int32_t ddd_enabled;   /* AdaEAGLE-DDD exit rule (Sec. 3.4, 4.2); greedy only */
+  float ddd_threshold;   /* log-probability threshold of that rule (the paper picks -0.6) */
 } ae_config;
 
 /* One pre-norm Llama-style decoder layer (device pointers). */
@@ -117,8 +119,13 @@ int ae_ldlp(ae_ctx *ctx, int *k_out, float *y_out);
 /* Eq. 2: draft catch-up over the newly validated slots, then a chain of k-1 further
  * one-row forwards; emits k tokens (argmax of the shared LM head, lowest id on ties;
  * with temperature > 0 inverse-CDF samples driven by u_draft[i] in [0,1)).
- * override_ids (host, nullable): entry i >= 0 replaces the i-th emitted token before it
- * is chained.  draft_ids_out (host, nullable) receives the k tokens. */
+ * override_ids (host, nullable, k_max entries when ddd_enabled else k): entry i >= 0
+ * replaces the i-th emitted token before it is chained.  draft_ids_out (host, nullable,
+ * room for k_max ids) receives the tokens.
+ * With cfg.ddd_enabled the head exits before token s iff s > k AND the log-probability of
+ * the s-1 tokens drafted so far is below cfg.ddd_threshold: at least one token is drafted,
+ * the longer of the two lengths is kept, never more than k_max; every decision past k costs
+ * one host synchronisation.  ae_last_draft_len() tells how many tokens were drafted. */
 int ae_draft(ae_ctx *ctx, int k, const int32_t *override_ids, const double *u_draft,
              int32_t *draft_ids_out);
 
@@ -126,6 +133,11 @@ int ae_draft(ae_ctx *ctx, int k, const int32_t *override_ids, const double *u_dr
  * attention over the cache; row i's logits judge block token i+1.  block_ids (host)
  * NULL => the block is [pending, the k draft tokens] and n_rows must be k+1. */
 int ae_verify(ae_ctx *ctx, const int32_t *block_ids, int n_rows);
+
+/* Number of tokens the last ae_draft emitted, and the log-probability of that sequence under
+ * the draft head (valid when cfg.ddd_enabled). */
+int ae_last_draft_len(const ae_ctx *ctx);
+int ae_get_draft_logprob(ae_ctx *ctx, float *out);
 
 /* Acceptance and rollback.  Greedy (temperature 0, u ignored): n_accepted = length of
  * the longest draft prefix equal to the target argmax, bonus = target argmax of the

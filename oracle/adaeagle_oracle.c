@@ -40,6 +40,7 @@ struct orc_model {
   int32_t *draft_ids;    /* [k_max] */
   int32_t *block;        /* [k_max+1] ids of the last verify block */
   int cur_k, block_rows;
+  double cum_logp;       /* log-probability of the current draft sequence */
   int have_pending, have_draft, have_verify;
 };
 
@@ -479,8 +480,8 @@ static int32_t pick_draft_token(orc_model *m, int i, const double *u_draft) {
 int orc_draft(orc_model *m, int k, const int32_t *override_ids, const double *u_draft, int32_t *ids_out) {
   const orc_config *c = &m->c;
   if (!m->have_pending) return -2;
-  if (k < 0 || k > c->k_max || m->kv_len + k + 1 > c->n_ctx_max) return -1;
-  if (c->temperature > 0.0f && k > 0 && !u_draft) return -1;
+  if (k < 0 || k > c->k_max || m->kv_len + c->k_max + 1 > c->n_ctx_max) return -1;
+  if (c->temperature > 0.0f && (k > 0 || c->ddd_enabled) && !u_draft) return -1;
   const int n = m->kv_len, d = c->d_model, V = c->vocab;
   const int catch_rows = n - m->dlen;
   if (catch_rows < 1 || catch_rows > m->nF) return -2;
@@ -488,7 +489,12 @@ int orc_draft(orc_model *m, int k, const int32_t *override_ids, const double *u_
   draft_rows(m, m->F + (size_t)(m->nF - catch_rows) * d, m->hist + m->dlen + 1, catch_rows, m->dlen);
   m->dlen = n;
   float *feat = (float *)malloc(sizeof(float) * d);
-  for (int i = 0; i < k; ++i) {
+  const double T = c->temperature > 0.0f ? (double)c->temperature : 1.0;
+  m->cum_logp = 0.0;
+  int i = 0;
+  for (; i < c->k_max; ++i) {
+    /* exit rule: past the predicted length, stop unless DDD says the sequence is still likely */
+    if (i >= k && !(c->ddd_enabled && m->cum_logp >= (double)c->ddd_threshold)) break;
     if (i > 0) { /* chain: the head's own previous output stands in for the feature */
       memcpy(feat, m->fhat, sizeof(float) * d);
       draft_rows(m, feat, &m->draft_ids[i - 1], 1, n - 1 + i);
@@ -501,7 +507,15 @@ int orc_draft(orc_model *m, int k, const int32_t *override_ids, const double *u_
     }
     m->draft_ids[i] = t;
     if (ids_out) ids_out[i] = t;
+    { /* log p_hat(t) under softmax(logits / T) */
+      const float *lg = m->dlogits + (size_t)i * V;
+      double mx = -INFINITY, se = 0.0;
+      for (int x = 0; x < V; ++x) if ((double)lg[x] > mx) mx = (double)lg[x];
+      for (int x = 0; x < V; ++x) se += exp(((double)lg[x] - mx) / T);
+      m->cum_logp += ((double)lg[t] - mx) / T - log(se);
+    }
   }
+  k = i;
   free(feat);
   m->cur_k = k;
   m->have_draft = 1;
@@ -556,6 +570,7 @@ int orc_step(orc_model *m, int k_force, const int32_t *override_ids, const doubl
   if ((rc = orc_ldlp(m, &k, NULL))) return rc;
   if (k_force >= 0) k = k_force;
   if ((rc = orc_draft(m, k, override_ids, u_draft, NULL))) return rc;
+  k = m->cur_k; /* DDD may have extended the draft */
   if ((rc = orc_verify(m, NULL, k + 1))) return rc;
   int acc = 0;
   int32_t b = 0;
@@ -584,6 +599,8 @@ int orc_ar_greedy(orc_model *m, int n_tokens, int32_t *out) {
 }
 
 int orc_kv_len(const orc_model *m) { return m->kv_len; }
+int orc_last_draft_len(const orc_model *m) { return m->cur_k; }
+double orc_draft_logprob(const orc_model *m) { return m->cum_logp; }
 int32_t orc_pending(const orc_model *m) { return m->hist[m->kv_len]; }
 const float *orc_logits(const orc_model *m, int row) { return m->logits + (size_t)row * m->c.vocab; }
 const float *orc_feature(const orc_model *m, int row) { return m->F + (size_t)row * m->c.d_model; }

@@ -45,6 +45,8 @@ typedef struct {
   int32_t ldlp_in_mode;  /* 0: input [e ; f] (2d, Sec. 3.2)   1: f only (d) */
   int32_t ldlp_hidden, ldlp_n_res;
   float temperature;     /* 0 => greedy */
+  int32_t ddd_enabled;   /* AdaEAGLE-DDD (Sec. 3.4): keep drafting past the predicted length ... */
+  float ddd_threshold;   /* ... while the draft sequence's log-probability is >= this value */
 } orc_config;
 
 /* One decoder layer: matrices row-major [out, in] in cfg.wdtype, norm gains float[d]. */
@@ -90,7 +92,10 @@ int orc_set_state(orc_model *m, int kv_len, int32_t last_tok, int32_t pending, c
 
 /* Eq. 3.  y_out (nullable) receives the raw scalar before rounding. */
 int orc_ldlp(orc_model *m, int *k_out, float *y_out);
-/* Eq. 2: catch-up over newly validated slots, then chain to k tokens.
+/* Eq. 2: catch-up over newly validated slots, then chain to k tokens.  With ddd_enabled
+ * (Sec. 3.4, 4.2) the head exits before token s iff s > k AND the log-probability of the
+ * s-1 tokens drafted so far is below ddd_threshold, so at least one token is drafted and
+ * the longer of the two lengths is kept; never more than k_max tokens.
  * override_ids[i] >= 0 replaces the i-th emitted token (nullable).
  * u_draft[i] in [0,1) drives sampling of the i-th token when temperature > 0. */
 int orc_draft(orc_model *m, int k, const int32_t *override_ids, const double *u_draft,
@@ -110,6 +115,8 @@ int orc_step(orc_model *m, int k_force, const int32_t *override_ids, const doubl
 int orc_ar_greedy(orc_model *m, int n_tokens, int32_t *out);
 
 int orc_kv_len(const orc_model *m);
+int orc_last_draft_len(const orc_model *m);      /* tokens actually drafted by the last orc_draft */
+double orc_draft_logprob(const orc_model *m);    /* log-probability of that draft sequence */
 int32_t orc_pending(const orc_model *m);
 const float *orc_logits(const orc_model *m, int row);        /* [V] of the last verify */
 const float *orc_feature(const orc_model *m, int row);       /* [d] */

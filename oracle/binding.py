@@ -19,7 +19,8 @@ class OrcConfig(C.Structure):
                 ("n_layers", "d_model", "n_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab")] + [
         ("rope_base", C.c_float), ("rms_eps", C.c_float), ("wdtype", C.c_int32),
         ("k_max", C.c_int32), ("n_ctx_max", C.c_int32), ("ldlp_in_mode", C.c_int32),
-        ("ldlp_hidden", C.c_int32), ("ldlp_n_res", C.c_int32), ("temperature", C.c_float)]
+        ("ldlp_hidden", C.c_int32), ("ldlp_n_res", C.c_int32), ("temperature", C.c_float),
+        ("ddd_enabled", C.c_int32), ("ddd_threshold", C.c_float)]
 
 
 class OrcLayer(C.Structure):
@@ -68,6 +69,8 @@ def load(acc_double=False):
         "orc_step": (I, [P, I, i32p, f64p, f64p, C.POINTER(I), C.POINTER(I), i32p]),
         "orc_ar_greedy": (I, [P, I, i32p]),
         "orc_kv_len": (I, [P]),
+        "orc_last_draft_len": (I, [P]),
+        "orc_draft_logprob": (D, [P]),
         "orc_pending": (C.c_int32, [P]),
         "orc_logits": (f32p, [P, I]),
         "orc_feature": (f32p, [P, I]),
@@ -193,10 +196,14 @@ class OracleModel:
         return k.value, y.value
 
     def draft(self, k, override_ids=None, u_draft=None):
-        out = np.zeros(max(k, 1), np.int32)
+        out = np.zeros(self.c.k_max + 1, np.int32)
         ov, ud = _i32(override_ids), _f64(u_draft)
         self._chk(self.lib.orc_draft(self.h, k, _ptr(ov, C.c_int32), _ptr(ud, C.c_double), _ptr(out, C.c_int32)), "orc_draft")
-        return out[:k]
+        return out[:self.lib.orc_last_draft_len(self.h)]
+
+    @property
+    def draft_logprob(self):
+        return self.lib.orc_draft_logprob(self.h)
 
     def verify(self, block_ids=None, n_rows=None):
         b = _i32(block_ids)

@@ -21,7 +21,7 @@ _CODES = {AE_EINVAL: "AE_EINVAL", AE_ESTATE: "AE_ESTATE", AE_ENOMEM: "AE_ENOMEM"
 EXPORTS = ("ae_init", "ae_free", "ae_last_error", "ae_prefill", "ae_kv_import", "ae_set_state", "ae_ldlp",
            "ae_draft", "ae_verify", "ae_accept", "ae_step", "ae_kv_len", "ae_pending", "ae_get_logits",
            "ae_get_feature", "ae_get_draft_logits", "ae_get_kv_row", "ae_set_profiling", "ae_get_phase_times",
-           "ae_set_kernel_timing", "ae_get_kernel_timing", "ae_version")
+           "ae_set_kernel_timing", "ae_get_kernel_timing", "ae_last_draft_len", "ae_get_draft_logprob", "ae_version")
 
 
 class AeConfig(C.Structure):
@@ -29,7 +29,8 @@ class AeConfig(C.Structure):
                 ("n_layers", "d_model", "n_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab")] + [
         ("rope_base", C.c_float), ("rms_eps", C.c_float), ("dtype", C.c_int32), ("k_max", C.c_int32),
         ("n_ctx_max", C.c_int32), ("ldlp_in_mode", C.c_int32), ("ldlp_hidden", C.c_int32),
-        ("ldlp_n_res", C.c_int32), ("temperature", C.c_float)]
+        ("ldlp_n_res", C.c_int32), ("temperature", C.c_float), ("ddd_enabled", C.c_int32),
+        ("ddd_threshold", C.c_float)]
 
 
 class AeLayerW(C.Structure):
@@ -88,6 +89,8 @@ def load_library(path=LIB_PATH):
         "ae_accept": (I, [P, f64p, C.POINTER(I), i32p]),
         "ae_step": (I, [P, C.POINTER(AeStepIO)]),
         "ae_kv_len": (I, [P]),
+        "ae_last_draft_len": (I, [P]),
+        "ae_get_draft_logprob": (I, [P, f32p]),
         "ae_pending": (C.c_int32, [P]),
         "ae_get_logits": (I, [P, I, f32p]),
         "ae_get_feature": (I, [P, I, f32p]),
@@ -193,11 +196,17 @@ class Engine:
         return k.value, y.value
 
     def draft(self, k, override_ids=None, u_draft=None, want_ids=True):
-        out = np.zeros(max(k, 1), np.int32)
+        out = np.zeros(self.cfg.k_max + 1, np.int32)
         ov, ud = _i32(override_ids), _f64(u_draft)
         self._chk(self.lib.ae_draft(self.h, k, _p(ov, C.c_int32), _p(ud, C.c_double),
                                     _p(out, C.c_int32) if want_ids else None), "ae_draft")
-        return out[:k]
+        return out[:self.lib.ae_last_draft_len(self.h)]
+
+    @property
+    def draft_logprob(self):
+        v = C.c_float()
+        self._chk(self.lib.ae_get_draft_logprob(self.h, C.byref(v)), "ae_get_draft_logprob")
+        return v.value
 
     def verify(self, block_ids=None, n_rows=None):
         b = _i32(block_ids)

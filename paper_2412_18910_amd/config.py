@@ -22,6 +22,8 @@ class Config:
     ldlp_hidden: int = 256
     ldlp_n_res: int = 0
     temperature: float = 0.0     # 0 => greedy
+    ddd_enabled: int = 0         # AdaEAGLE-DDD exit rule (Sec. 3.4)
+    ddd_threshold: float = -0.6  # log-probability threshold (Sec. 4.3.3)
 
     def dict(self):
         return asdict(self)

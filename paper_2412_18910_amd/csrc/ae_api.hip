@@ -268,7 +268,8 @@ int ae_init(const ae_config *cfg, const ae_weights *w, void *hip_stream, ae_ctx 
   if (g.n_layers < 1 || g.d_model < 8 || g.n_heads < 1 || g.n_kv_heads < 1 || g.d_ffn < 8 || g.vocab < 1 ||
       g.n_heads % g.n_kv_heads != 0 || g.k_max < 0 || g.n_ctx_max < 1 || g.ldlp_hidden < 1 || g.ldlp_n_res < 0 ||
       (g.dtype != AE_BF16 && g.dtype != AE_FP32) || (g.ldlp_in_mode != 0 && g.ldlp_in_mode != 1) ||
-      !(g.temperature >= 0.f) || !(g.rms_eps >= 0.f) || !(g.rope_base > 0.f))
+      !(g.temperature >= 0.f) || !(g.rms_eps >= 0.f) || !(g.rope_base > 0.f) ||
+      (g.ddd_enabled != 0 && g.ddd_enabled != 1) || (g.ddd_enabled && !(g.ddd_threshold == g.ddd_threshold)))
     return fail(nullptr, AE_EINVAL, "ae_init: configuration field out of range");
   if (g.head_dim != 64 && g.head_dim != 128) return fail(nullptr, AE_EUNSUPPORTED, "head_dim must be 64 or 128");
   if (g.k_max + 1 > kMaxRows) return fail(nullptr, AE_EUNSUPPORTED, "k_max must be <= 15");
@@ -276,6 +277,8 @@ int ae_init(const ae_config *cfg, const ae_weights *w, void *hip_stream, ae_ctx 
     return fail(nullptr, AE_EUNSUPPORTED, "d_model, d_ffn, ldlp_hidden must be multiples of 8 (ldlp_hidden <= 1024)");
   if ((g.n_heads / g.n_kv_heads) * kMaxRows > 64)
     return fail(nullptr, AE_EUNSUPPORTED, "n_heads / n_kv_heads must be <= 4");
+  if (g.ddd_enabled && g.temperature > 0.f)
+    return fail(nullptr, AE_EUNSUPPORTED, "the DDD exit rule is implemented for greedy decoding only");
   if (g.n_ctx_max > kMaxSplits * kAttnChunk) return fail(nullptr, AE_EUNSUPPORTED, "n_ctx_max too large (<= 16384)");
   if (!w->tok_emb || !w->final_norm || !w->lm_head || !w->layers || !w->draft_fc_w || !w->ldlp_w_in ||
       !w->ldlp_b_in || !w->ldlp_w_out || !w->ldlp_b_out || (g.ldlp_n_res > 0 && (!w->ldlp_w_res || !w->ldlp_b_res)))
@@ -505,18 +508,19 @@ int ae_draft(ae_ctx *c, int k, const int32_t *override_ids, const double *u_draf
   const ae_config &g = c->cfg;
   if (!c->have_pending) return fail(c, AE_ESTATE, "ae_draft: no pending token (prefill first)");
   if (k < 0 || k > g.k_max) return fail(c, AE_EINVAL, "ae_draft: k outside [0, k_max]");
-  if (c->kv_len + k + 1 > g.n_ctx_max) return fail(c, AE_EINVAL, "ae_draft: KV capacity exceeded");
+  if (c->kv_len + g.k_max + 1 > g.n_ctx_max) return fail(c, AE_EINVAL, "ae_draft: KV capacity exceeded");
   const int n = c->kv_len, catch_rows = n - c->dlen;
   if (catch_rows < 1 || catch_rows > c->nF)
     return fail(c, AE_ESTATE, "ae_draft: draft cache is stale (target advanced without the draft head)");
+  const int n_ov = g.ddd_enabled ? g.k_max : k;   // DDD may extend the draft up to k_max tokens
   if (override_ids)
-    for (int i = 0; i < k; ++i)
+    for (int i = 0; i < n_ov; ++i)
       if (override_ids[i] >= g.vocab) return fail(c, AE_EINVAL, "ae_draft: override id out of range");
   if (g.temperature > 0.f && k > 0 && !u_draft) return fail(c, AE_EINVAL, "ae_draft: temperature > 0 needs u_draft");
   hipStream_t s = c->stream;
   // upload the override table (-1 = keep the head's own token) and the sampling uniforms
   DevState *up = (DevState *)c->h_ids;
-  for (int i = 0; i < kMaxRows; ++i) up->override_ids[i] = (override_ids && i < k) ? override_ids[i] : -1;
+  for (int i = 0; i < kMaxRows; ++i) up->override_ids[i] = (override_ids && i < n_ov) ? override_ids[i] : -1;
   HIPCHK(c, hipMemcpyAsync(c->st->override_ids, up->override_ids, sizeof(up->override_ids), hipMemcpyHostToDevice, s));
   if (g.temperature > 0.f && k > 0) {
     for (int i = 0; i < k; ++i) {
@@ -530,15 +534,30 @@ int ae_draft(ae_ctx *c, int k, const int32_t *override_ids, const double *u_draf
   c->dlen = n;
   const float *fh = c->x + (size_t)(catch_rows - 1) * g.d_model;
   int fh_row = catch_rows - 1;
-  for (int i = 0; i < k; ++i) {
+  int i = 0;
+  float cum = 0.f;   // log-probability of the tokens drafted so far (host copy, DDD only)
+  for (; i < g.k_max; ++i) {
+    if (i >= k) {
+      // past the predicted length: exit unless the DDD rule says the sequence is still likely
+      if (!g.ddd_enabled) break;
+      if (i > 0) {
+        int rc = read_state(c);
+        if (rc) return rc;
+        cum = c->h_st->cum_logp;
+      }
+      if (!(cum >= g.ddd_threshold)) break;
+    }
     if (i > 0) {  // chain: the head's previous output replaces the feature
       draft_rows(c, fh, g.d_model, c->st->draft_ids + (i - 1), 1, n - 1 + i);
       fh = c->x;
       fh_row = 0;
     }
     draft_lm_head(c, fh_row, i);
+    if (g.ddd_enabled) launch_draft_logprob(c->dlogits + (size_t)i * g.vocab, g.vocab, c->st, i, s);
   }
+  k = i;
   c->cur_k = k;
+  c->cur_k_last = k;
   c->have_draft = true;
   c->have_verify = false;
   if (out && k > 0) {
@@ -627,6 +646,7 @@ int ae_step(ae_ctx *c, ae_step_io *io) {
   }
   if (prof) hipEventRecord(c->ev[1], s);
   if ((rc = ae_draft(c, k, io->override_ids, io->u_draft, nullptr))) return rc;
+  k = c->cur_k;   // the DDD rule may have extended the draft
   if (prof) hipEventRecord(c->ev[2], s);
   if ((rc = ae_verify(c, nullptr, k + 1))) return rc;
   if (prof) hipEventRecord(c->ev[3], s);
@@ -650,6 +670,16 @@ int ae_step(ae_ctx *c, ae_step_io *io) {
 }
 
 int ae_kv_len(const ae_ctx *c) { return c ? c->kv_len : AE_EINVAL; }
+int ae_last_draft_len(const ae_ctx *c) { return c ? c->cur_k_last : AE_EINVAL; }
+
+int ae_get_draft_logprob(ae_ctx *c, float *out) {
+  if (!c) return AE_EINVAL;
+  if (!out) return fail(c, AE_EINVAL, "ae_get_draft_logprob: NULL output");
+  int rc = read_state(c);
+  if (rc) return rc;
+  *out = c->h_st->cum_logp;
+  return AE_OK;
+}
 int32_t ae_pending(const ae_ctx *c) { return c && c->have_pending ? c->pending : -1; }
 
 static int copy_out(ae_ctx *c, const float *src, size_t n, float *dst) {

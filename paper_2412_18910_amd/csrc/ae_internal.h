@@ -28,6 +28,8 @@ struct DevState {
   int32_t argmax[kMaxRows]; // per-row argmax of the last LM-head call
   double u_draft[kMaxRows];
   double u_accept[kMaxRows];
+  float cum_logp;           // log-probability of the current draft sequence (DDD exit rule)
+  float draft_lp[kMaxRows]; // per-token log-probabilities
 };
 
 // Weight matrix handle: row-major source plus (bf16 fast path) the re-tiled copy.
@@ -92,7 +94,7 @@ struct ae_ctx {
 
   // host-side state machine
   int kv_len = 0, dlen = 0, nF = 0;
-  int cur_k = 0, block_rows = 0;
+  int cur_k = 0, cur_k_last = 0, block_rows = 0;
   int32_t pending = 0;
   bool have_pending = false, have_draft = false, have_verify = false, k_next_valid = false;
   int k_next = 0;
@@ -126,6 +128,8 @@ void launch_argmax(const float *logits, int rows, int V, int32_t *out_ids, hipSt
 void launch_draft_cat(const float *feat, int feat_ld, const void *emb, int dtype, const int32_t *next_ids,
                       int rows, int d, float *cat, hipStream_t s);
 void launch_pick_draft(DevState *st, int i, int32_t *hist_slot, hipStream_t s);
+// log softmax(logits)[draft token i] -> st->draft_lp[i], added to st->cum_logp (reset when i == 0)
+void launch_draft_logprob(const float *logits, int V, DevState *st, int i, hipStream_t s);
 void launch_build_block(DevState *st, const int32_t *hist, int kv_len, int k, hipStream_t s);
 void launch_accept_greedy(DevState *st, int32_t *hist, int kv_len, int rows, hipStream_t s);
 void launch_ldlp_gather(const void *emb, int dtype, const int32_t *hist, const float *F, int d, int in_mode,

@@ -203,6 +203,39 @@ __global__ void pick_draft_kernel(DevState *st, int i) {
 }
 void launch_pick_draft(DevState *st, int i, int32_t *, hipStream_t s) { pick_draft_kernel<<<1, 1, 0, s>>>(st, i); }
 
+// AdaEAGLE-DDD bookkeeping: log-probability of draft token i under softmax(logits), one
+// workgroup, fixed-shape reductions.
+__global__ __launch_bounds__(1024) void draft_logprob_kernel(const float *logits, int V, DevState *st, int i) {
+  __shared__ float sh[1024];
+  const int t = threadIdx.x;
+  float mx = -INFINITY;
+  for (int x = t; x < V; x += 1024) mx = fmaxf(mx, logits[x]);
+  sh[t] = mx;
+  __syncthreads();
+  for (int o = 512; o > 0; o >>= 1) {
+    if (t < o) sh[t] = fmaxf(sh[t], sh[t + o]);
+    __syncthreads();
+  }
+  mx = sh[0];
+  __syncthreads();
+  float se = 0.f;
+  for (int x = t; x < V; x += 1024) se += expf(logits[x] - mx);
+  sh[t] = se;
+  __syncthreads();
+  for (int o = 512; o > 0; o >>= 1) {
+    if (t < o) sh[t] += sh[t + o];
+    __syncthreads();
+  }
+  if (t == 0) {
+    const float lp = logits[st->draft_ids[i]] - mx - logf(sh[0]);
+    st->draft_lp[i] = lp;
+    st->cum_logp = (i == 0 ? 0.f : st->cum_logp) + lp;
+  }
+}
+void launch_draft_logprob(const float *logits, int V, DevState *st, int i, hipStream_t s) {
+  draft_logprob_kernel<<<1, 1024, 0, s>>>(logits, V, st, i);
+}
+
 __global__ void build_block_kernel(DevState *st, const int32_t *hist, int kv_len, int k) {
   if (threadIdx.x == 0) st->block[0] = hist[kv_len];
   if ((int)threadIdx.x < k) st->block[1 + threadIdx.x] = st->draft_ids[threadIdx.x];

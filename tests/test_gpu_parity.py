@@ -401,3 +401,40 @@ def test_13b_shape_reduced_depth_step_matches_oracle():
     cfg = LLAMA_13B.with_(n_layers=2, n_ctx_max=3000 + 64)
     worst = _full_size_step(cfg, 4, 3000, ks=[10, 0, 6])
     assert worst < 2e-2
+
+
+@pytest.mark.parametrize("cfg0,seed", [(TINY, 12), (MED_BF16, 13)], ids=["fp32", "bf16"])
+def test_ddd_exit_rule_matches_oracle(cfg0, seed):
+    """AdaEAGLE-DDD: the draft keeps going past the predicted length while the sequence
+    log-probability stays above the threshold; lengths, tokens and the log-probability match."""
+    probe_cfg = cfg0.with_(ddd_enabled=1, ddd_threshold=-1e9)
+    eng, orc, w = make_pair(probe_cfg, seed)
+    ids = synth.token_ids(40, probe_cfg.vocab, seed + 200)
+    orc.prefill(ids)
+    eng.prefill(ids)
+    d_o = orc.draft(0)
+    d_g = eng.draft(0, override_ids=np.concatenate([d_o, -np.ones(probe_cfg.k_max, np.int32)])[:probe_cfg.k_max])
+    assert len(d_o) == len(d_g) == probe_cfg.k_max            # threshold -1e9: always k_max tokens
+    assert abs(orc.draft_logprob - eng.draft_logprob) < (1e-3 if cfg0.dtype == FP32 else 5e-2)
+    cums = np.cumsum([float(np.log(np.exp(orc.draft_logits(i).astype(np.float64) - orc.draft_logits(i).max()).sum()) * -1
+                            + orc.draft_logits(i)[int(t)] - orc.draft_logits(i).max()) for i, t in enumerate(d_o)])
+    eng.close()
+    # thresholds half way between consecutive cumulative log-probabilities: no decision near a tie
+    for cut, k in [(1, 0), (3, 2), (5, 5), (2, 6)]:
+        theta = float(0.5 * (cums[cut] + cums[cut + 1]))
+        cfg = cfg0.with_(ddd_enabled=1, ddd_threshold=theta)
+        eng, orc, _ = make_pair(cfg, seed)
+        orc.prefill(ids)
+        eng.prefill(ids)
+        want = orc.draft(k)
+        got = eng.draft(k, override_ids=np.concatenate([want, -np.ones(cfg.k_max, np.int32)])[:cfg.k_max])
+        assert len(want) == max(k, cut + 2), (cut, k, len(want))
+        assert np.array_equal(got, want)
+        # a full step: verify block of (drafted + 1) rows, accept, next prediction
+        orc.verify(n_rows=len(want) + 1)
+        eng.verify(n_rows=len(got) + 1)
+        lo, lg = orc.logits(len(want)), eng.logits(len(got))
+        assert np.max(np.abs(lo - lg)) <= TOL[cfg.dtype]
+        if all(top2_margin(orc.logits(r)) > MARGIN for r in range(len(want) + 1)):
+            assert orc.accept() == eng.accept()
+        eng.close()

@@ -176,3 +176,64 @@ def test_state_errors():
         m.draft(TINY.k_max + 1)
     with pytest.raises(OracleError):
         m.verify([TINY.vocab])        # id out of range
+
+
+# ---------------------------------------------------------------- AdaEAGLE-DDD exit rule (Sec. 3.4, 4.2)
+
+def _ddd_model(theta, w=None, seed=0):
+    cfg = TINY.with_(ddd_enabled=1, ddd_threshold=theta)
+    m, w = make_oracle(cfg, seed, weights=w)
+    m.prefill(synth.token_ids(24, cfg.vocab, 300))
+    return cfg, m, w
+
+
+def test_ddd_sequence_logprob_matches_library_log_softmax():
+    cfg, m, w = _ddd_model(-1e9)            # threshold never reached: always drafts k_max tokens
+    ids = m.draft(2)
+    assert len(ids) == cfg.k_max
+    want = 0.0
+    for i, t in enumerate(ids):
+        lp = torch.log_softmax(torch.from_numpy(m.draft_logits(i)).double(), -1)
+        want += float(lp[int(t)])
+        assert int(t) == int(lp.argmax())   # greedy draft token
+    assert abs(m.draft_logprob - want) < 1e-6
+
+
+def test_ddd_keeps_the_longer_of_the_two_lengths():
+    # reference lengths from an unconstrained run: cumulative log-probabilities c_1 > c_2 > ...
+    cfg, m, w = _ddd_model(-1e9)
+    ids = m.draft(0)
+    cums = np.cumsum([float(torch.log_softmax(torch.from_numpy(m.draft_logits(i)).double(), -1)[int(t)])
+                      for i, t in enumerate(ids)])
+    assert np.all(np.diff(cums) < 0)
+    # threshold between c_3 and c_4: the rule stops before token s iff s > k and c_{s-1} < theta,
+    # so the DDD length is 4 (c_3 >= theta lets token 4 through, c_4 < theta stops token 5)
+    theta = 0.5 * (cums[2] + cums[3])
+    for k, want in [(0, 4), (2, 4), (4, 4), (6, 6), (cfg.k_max, cfg.k_max)]:
+        _, m2, _ = _ddd_model(theta, w)
+        got = m2.draft(k)
+        assert len(got) == want, (k, len(got))
+        assert np.array_equal(got, ids[:want])
+        assert abs(m2.draft_logprob - cums[want - 1]) < 1e-6
+    # a threshold above 0 can never be met by a log-probability: only the predicted length remains,
+    # except that the empty sequence (log-probability 0) is compared too
+    _, m3, _ = _ddd_model(1e-3, w)
+    assert len(m3.draft(3)) == 3
+    _, m4, _ = _ddd_model(1e-3, w)
+    assert len(m4.draft(0)) == 0
+    _, m5, _ = _ddd_model(-1e-9, w)          # empty sequence passes (0 >= theta): at least one token
+    assert len(m5.draft(0)) == 1
+
+
+def test_ddd_run_stays_lossless(ar_reference):
+    ids, w, _, ar = ar_reference
+    cfg = TINY.with_(ddd_enabled=1, ddd_threshold=-8.0)
+    m, _ = make_oracle(cfg, 0, weights=w)
+    m.prefill(ids)
+    out, ks = [], []
+    while len(out) < 64:
+        k, na, toks = m.step()
+        out.extend(int(t) for t in toks)
+        ks.append(k)
+    assert np.array_equal(np.array(out[:64]), ar[:64])
+    assert max(ks) >= 1
