@@ -438,3 +438,68 @@ def test_ddd_exit_rule_matches_oracle(cfg0, seed):
         if all(top2_margin(orc.logits(r)) > MARGIN for r in range(len(want) + 1)):
             assert orc.accept() == eng.accept()
         eng.close()
+
+
+EDGE_BF16 = Config(2, 256, 4, 2, 64, 512, 1024, dtype=BF16, k_max=15, n_ctx_max=1024, ldlp_hidden=64)
+
+
+@pytest.mark.parametrize("n_ctx", [1, 15, 16, 17, 255, 256, 257, 511, 513])
+def test_context_lengths_around_tile_and_chunk_boundaries(n_ctx):
+    """Cached lengths next to the 16/32-slot cache tiles and the 256-key attention chunks, with
+    the widest block (k_max = 15: 16 rows, group size 2) so that blocks straddle the boundaries."""
+    cfg = EDGE_BF16
+    eng, orc, _ = make_pair(cfg, 20)
+    for layer in range(cfg.n_layers + 1):
+        k, v = synth.kv_fill(cfg, n_ctx, 30 + n_ctx, layer)
+        orc.kv_import(layer, k, v)
+        eng.kv_import(layer, k, v)
+    feat = synth.feature_row(cfg, 21)
+    orc.set_state(n_ctx, 3, 4, feat)
+    eng.set_state(n_ctx, 3, 4, feat)
+    for k in (15, 0, 7):
+        d_o = orc.draft(k)
+        d_g = eng.draft(k, override_ids=d_o if k else None)
+        assert np.array_equal(d_o, d_g)
+        orc.verify(n_rows=k + 1)
+        eng.verify(n_rows=k + 1)
+        for row in range(k + 1):
+            assert np.max(np.abs(orc.logits(row) - eng.logits(row))) <= 2e-2, (n_ctx, k, row)
+        ao, ag = orc.accept(), eng.accept()
+        if ao != ag:      # only possible on a row without a clear winner
+            break
+    eng.close()
+
+
+def test_capacity_limits_are_enforced():
+    cfg = EDGE_BF16.with_(n_ctx_max=64, k_max=7)
+    eng, _, _ = make_pair(cfg, 22)
+    with pytest.raises(AdaEagleError) as e:
+        eng.prefill(np.zeros(57, np.int32))        # 57 + k_max + 1 > 64
+    assert e.value.code == AE_EINVAL
+    eng.prefill(np.zeros(56, np.int32))            # exactly fits one more widest block
+    assert eng.kv_len == 56
+    k, na, toks = eng.step(k_force=7)
+    assert eng.kv_len == 56 + na + 1
+    with pytest.raises(AdaEagleError) as e:        # the next widest block would overflow the cache
+        eng.step(k_force=7)
+    assert e.value.code == AE_EINVAL
+    eng.close()
+
+
+def test_two_contexts_are_independent():
+    cfg = TINY
+    eng_a, orc, w = make_pair(cfg, 23)
+    from .gpu_helpers import to_device
+    from paper_2412_18910_amd.binding import Engine
+    eng_b = Engine(cfg, to_device(w))
+    ids_a, ids_b = synth.token_ids(20, cfg.vocab, 1), synth.token_ids(31, cfg.vocab, 2)
+    eng_a.prefill(ids_a)
+    eng_b.prefill(ids_b)
+    orc.prefill(ids_a)
+    for _ in range(6):                              # interleave the two sequences
+        ta = eng_a.step(k_force=3)
+        eng_b.step(k_force=5)
+        to = orc.step(k_force=3)
+        assert ta[1] == to[1] and np.array_equal(ta[2], to[2])
+    eng_a.close()
+    eng_b.close()
