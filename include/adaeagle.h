@@ -98,9 +98,20 @@ void ae_free(ae_ctx *ctx);
 const char *ae_last_error(const ae_ctx *ctx);
 
 /* First iteration of Algorithm 1 (k = 0, T = prompt): runs the n prompt tokens (host
- * ids) through the target in blocks of <= 16 rows and through the draft head for every
- * slot whose next token is known; leaves kv_len = n and pending = first new token. */
+ * ids) through the target and through the draft head for every slot whose next token is
+ * known; leaves kv_len = n and pending = first new token.  Short prompts go through the
+ * decode kernels in blocks of <= 16 rows; bf16 prompts of >= 64 tokens take the dense pass
+ * (matrix-core bound GEMMs over chunks of up to chunk_rows rows, causal attention straight
+ * off the cache; the draft head only needs its K/V rows there).  Both give the same state
+ * up to rounding order. */
 int ae_prefill(ae_ctx *ctx, const int32_t *prompt_ids, int n);
+
+/* How ae_prefill runs.  mode: AE_PREFILL_AUTO (default, rule above), AE_PREFILL_BLOCKS
+ * (always the 16-row decode kernels) or AE_PREFILL_DENSE (always the dense pass;
+ * AE_EUNSUPPORTED for fp32 weights).  chunk_rows: rows per dense pass, a multiple of 128
+ * in [128, 8192], or 0 to keep the current value (default 2048). */
+enum { AE_PREFILL_AUTO = 0, AE_PREFILL_BLOCKS = 1, AE_PREFILL_DENSE = 2 };
+int ae_set_prefill_mode(ae_ctx *ctx, int mode, int chunk_rows);
 
 /* Test / benchmark set-up: install K and V rows (host float [n][n_kv_heads*head_dim],
  * converted to the cache dtype) for layer `layer` (n_layers = the draft layer) at

@@ -21,7 +21,7 @@ _CODES = {AE_EINVAL: "AE_EINVAL", AE_ESTATE: "AE_ESTATE", AE_ENOMEM: "AE_ENOMEM"
 EXPORTS = ("ae_init", "ae_free", "ae_last_error", "ae_prefill", "ae_kv_import", "ae_set_state", "ae_ldlp",
            "ae_draft", "ae_verify", "ae_accept", "ae_step", "ae_kv_len", "ae_pending", "ae_get_logits",
            "ae_get_feature", "ae_get_draft_logits", "ae_get_kv_row", "ae_set_profiling", "ae_get_phase_times",
-           "ae_set_kernel_timing", "ae_get_kernel_timing", "ae_last_draft_len", "ae_get_draft_logprob", "ae_version")
+           "ae_set_kernel_timing", "ae_get_kernel_timing", "ae_last_draft_len", "ae_get_draft_logprob", "ae_set_prefill_mode", "ae_version")
 
 
 class AeConfig(C.Structure):
@@ -99,6 +99,7 @@ def load_library(path=LIB_PATH):
         "ae_set_profiling": (I, [P, I]),
         "ae_get_phase_times": (I, [P, C.POINTER(AePhaseTimes)]),
         "ae_set_kernel_timing": (I, [P, I]),
+        "ae_set_prefill_mode": (I, [P, I, I]),
         "ae_get_kernel_timing": (I, [P, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
         "ae_version": (C.c_char_p, []),
     }
@@ -255,6 +256,11 @@ class Engine:
 
     def set_profiling(self, on=True):
         self._chk(self.lib.ae_set_profiling(self.h, int(on)), "ae_set_profiling")
+
+    PREFILL_AUTO, PREFILL_BLOCKS, PREFILL_DENSE = 0, 1, 2
+
+    def set_prefill_mode(self, mode, chunk_rows=0):
+        self._chk(self.lib.ae_set_prefill_mode(self.h, int(mode), int(chunk_rows)), "ae_set_prefill_mode")
 
     def set_kernel_timing(self, on=True):
         self._chk(self.lib.ae_set_kernel_timing(self.h, int(on)), "ae_set_kernel_timing")

@@ -241,6 +241,124 @@ int read_state(ae_ctx *c) {
   return AE_OK;
 }
 
+// ---- dense prompt pass --------------------------------------------------------------
+// the dense GEMM's workgroup tile spans 256 output rows
+bool dense_ok(const ae_ctx *c) {
+  const ae_config &g = c->cfg;
+  return c->fast && g.d_model >= 256 && 2 * g.d_ffn >= 256 && (g.n_heads + 2 * g.n_kv_heads) * g.head_dim >= 256;
+}
+
+// Chunk buffers for `cap` rows (a multiple of 128): float residual stream and queries, the
+// packed inputs of the five GEMMs, RMSNorm partial sums and 1/rms.  Zero-filled so that the
+// padding rows of a chunk are finite.
+int ensure_dense(ae_ctx *c, int n) {
+  const ae_config &g = c->cfg;
+  const int want = ((n < c->dense_chunk ? n : c->dense_chunk) + 127) / 128 * 128;
+  if (want <= c->dense_cap) return AE_OK;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  for (void *p : c->dense_owned) hipFree(p);
+  c->dense_owned.clear();
+  c->dense_cap = 0;
+  const size_t cap = want, d = g.d_model, dq = (size_t)g.n_heads * g.head_dim, f = g.d_ffn;
+  struct { void **p; size_t bytes; } bufs[] = {
+      {(void **)&c->px, cap * d * 4},      {(void **)&c->pq, cap * dq * 4},   {(void **)&c->prinv, cap * 4},
+      {(void **)&c->pssq_a, cap * d * 4 / 16 * 1 + cap * 4}, {(void **)&c->pssq_f, cap * d * 4 / 16 + cap * 4},
+      {&c->pxa, cap * d * 4},              {&c->pxf, cap * d * 4},            {&c->pxatt, cap * dq * 4},
+      {&c->pxh, cap * f * 4},              {&c->pxcat, cap * 2 * d * 4}};
+  for (auto &b : bufs) {
+    void *q = nullptr;
+    const size_t bytes = (b.bytes + 255) / 256 * 256;
+    hipError_t e = hipMalloc(&q, bytes);
+    if (e != hipSuccess) return fail(c, AE_ENOMEM, std::string("dense prefill buffers: ") + hipGetErrorString(e));
+    c->dense_owned.push_back(q);
+    *b.p = q;
+    launch_fill_zero(q, bytes, c->stream);
+  }
+  c->dense_cap = want;
+  return AE_OK;
+}
+
+// Target layers over chunk rows [p0, p0+rows) and the draft head's K/V rows for the first
+// `drows` of them (the slots whose next token is in the prompt).
+void dense_chunk(ae_ctx *c, int p0, int rows, int drows) {
+  const ae_config &g = c->cfg;
+  hipStream_t s = c->stream;
+  const int d = g.d_model, dq = g.n_heads * g.head_dim, dkv = g.n_kv_heads * g.head_dim, f = g.d_ffn;
+  const int RB = c->dense_cap / 16, RBu = (rows + 15) / 16, Pd = d / 16, cap = kv_capacity(g);
+  launch_embed_dense(c->tok_emb, c->hist + p0, rows, d, c->layers[0].attn_norm, c->px, c->pxa, RB, c->pssq_a, s);
+  int Pa = 1;
+  auto qkv_pass = [&](int li, int nrows) {
+    const LayerW &w = c->layers[li];
+    launch_rinv_finalize(c->pssq_a, (nrows + 15) / 16, Pa, d, g.rms_eps, c->prinv, s);
+    GemmLaunch qkv;
+    qkv.W = &w.f_qkv; qkv.Xp = c->pxa; qkv.rows = nrows; qkv.epi = EPI_QKV; qkv.nseg = 3;
+    qkv.Y[0] = c->pq; qkv.ldy[0] = dq;
+    qkv.seg_N[0] = dq; qkv.seg_N[1] = dkv; qkv.seg_N[2] = dkv;
+    qkv.rope_tab = c->rope_tab; qkv.Kc = kv_layer_ptr(c, li); qkv.Vc = (char *)kv_layer_ptr(c, li) + c->kv_v_offset;
+    qkv.pos0 = p0; qkv.n_ctx = cap; qkv.hd = g.head_dim;
+    launch_gemm_dense(qkv, RB, c->prinv, s);
+  };
+  for (int l = 0; l < g.n_layers; ++l) {
+    const LayerW &w = c->layers[l];
+    qkv_pass(l, rows);
+    launch_attention_prefill(c->pq, rows, p0, g, kv_layer_ptr(c, l), c->kv_v_offset, c->pxatt, RB, s);
+    GemmLaunch o;
+    o.W = &w.wo; o.Xp = c->pxatt; o.rows = rows; o.epi = EPI_RESID; o.Y[0] = c->px; o.ldy[0] = d; o.seg_N[0] = d;
+    o.Xp_out = c->pxf; o.gain_out = w.ffn_norm; o.ssq_out = c->pssq_f;
+    launch_gemm_dense(o, RB, nullptr, s);
+    launch_rinv_finalize(c->pssq_f, RBu, Pd, d, g.rms_eps, c->prinv, s);
+    GemmLaunch gu;
+    gu.W = &w.f_gu; gu.Xp = c->pxf; gu.rows = rows; gu.epi = EPI_SWIGLU; gu.Xp_out = c->pxh; gu.seg_N[0] = 2 * f;
+    launch_gemm_dense(gu, RB, c->prinv, s);
+    GemmLaunch dn;
+    dn.W = &w.w_down; dn.Xp = c->pxh; dn.rows = rows; dn.epi = EPI_RESID; dn.Y[0] = c->px; dn.ldy[0] = d; dn.seg_N[0] = d;
+    dn.Xp_out = c->pxa; dn.gain_out = l + 1 < g.n_layers ? c->layers[l + 1].attn_norm : c->final_norm;
+    dn.ssq_out = c->pssq_a;
+    launch_gemm_dense(dn, RB, nullptr, s);
+    Pa = Pd;
+  }
+  if (drows > 0) {
+    // Eq. 2 catch-up of prompt slots: only the head's K/V rows are ever read again
+    const LayerW &dl = c->layers[g.n_layers];
+    launch_draft_cat_dense(c->px, drows, d, c->final_norm, g.rms_eps, c->tok_emb, c->hist + p0 + 1, c->pxcat, RB, s);
+    GemmLaunch fc;
+    fc.W = &c->draft_fc; fc.Xp = c->pxcat; fc.rows = drows; fc.epi = EPI_STORE; fc.bias = c->draft_fc_b;
+    fc.seg_N[0] = d; fc.ldy[0] = d;
+    fc.Xp_out = c->pxa; fc.gain_out = dl.attn_norm; fc.ssq_out = c->pssq_a;
+    launch_gemm_dense(fc, RB, nullptr, s);
+    Pa = Pd;
+    qkv_pass(g.n_layers, drows);
+  }
+}
+
+// Whole prompt through the dense pass; leaves the last position's feature in F row
+// (n-1) % 16 (where the 16-row path leaves it) and its logits / argmax in row 0.
+int prefill_dense(ae_ctx *c, int n) {
+  const ae_config &g = c->cfg;
+  hipStream_t s = c->stream;
+  int rc = ensure_dense(c, n);
+  if (rc) return rc;
+  int last_rows = 0;
+  for (int p0 = 0; p0 < n; p0 += c->dense_cap) {
+    const int rows = n - p0 < c->dense_cap ? n - p0 : c->dense_cap;
+    const bool last = p0 + rows == n;
+    dense_chunk(c, p0, rows, last ? rows - 1 : rows);
+    last_rows = rows;
+  }
+  const int frow = (n - 1) % kMaxRows;
+  float *F = c->F + (size_t)frow * g.d_model;
+  launch_rmsnorm(c->px + (size_t)(last_rows - 1) * g.d_model, c->final_norm, 1, g.d_model, g.rms_eps, F, s);
+  launch_pack_rows(F, g.d_model, 1, g.d_model, nullptr, c->xp_a, s);
+  GemmLaunch lm;
+  lm.W = &c->lm_head; lm.Xp = c->xp_a; lm.rows = 1; lm.epi = EPI_STORE;
+  lm.Y[0] = c->logits; lm.ldy[0] = g.vocab; lm.seg_N[0] = g.vocab;
+  lm.amax_val = c->amax_val; lm.amax_idx = c->amax_idx;
+  launch_gemm_mfma(lm, s);
+  launch_argmax_finish(c->amax_val, c->amax_idx, g.vocab / 16, 1, c->st, -1, s);
+  c->nF = frow + 1;
+  return AE_OK;
+}
+
 __global__ void finish_prefill_kernel(DevState *st, int32_t *hist, int n) {
   hist[n] = st->argmax[0];
   st->bonus = st->argmax[0];
@@ -412,6 +530,7 @@ void ae_free(ae_ctx *c) {
   if (!c) return;
   hipStreamSynchronize(c->stream);
   for (void *p : c->owned) hipFree(p);
+  for (void *p : c->dense_owned) hipFree(p);
   if (c->h_st) hipHostFree(c->h_st);
   if (c->h_ids) hipHostFree(c->h_ids);
   for (auto &e : c->ev)
@@ -431,13 +550,19 @@ int ae_prefill(ae_ctx *c, const int32_t *ids, int n) {
   memcpy(c->h_hist.data(), ids, sizeof(int32_t) * n);
   c->kv_len = 0; c->dlen = 0; c->nF = 0;
   c->have_pending = c->have_draft = c->have_verify = c->k_next_valid = false;
-  for (int p0 = 0; p0 < n; p0 += kMaxRows) {
-    const int rows = n - p0 < kMaxRows ? n - p0 : kMaxRows;
-    const bool last = p0 + rows == n;
-    target_forward(c, c->hist + p0, rows, p0, last ? rows - 1 : rows);
-    const int drows = last ? rows - 1 : rows;  // slots whose next token is in the prompt
-    if (drows > 0) draft_rows(c, c->F, g.d_model, c->hist + p0 + 1, drows, p0);
-    c->nF = rows;
+  const bool dense = c->prefill_mode == AE_PREFILL_DENSE || (c->prefill_mode == AE_PREFILL_AUTO && dense_ok(c) && n >= kDenseMinPrompt);
+  if (dense) {
+    int rc = prefill_dense(c, n);
+    if (rc) return rc;
+  } else {
+    for (int p0 = 0; p0 < n; p0 += kMaxRows) {
+      const int rows = n - p0 < kMaxRows ? n - p0 : kMaxRows;
+      const bool last = p0 + rows == n;
+      target_forward(c, c->hist + p0, rows, p0, last ? rows - 1 : rows);
+      const int drows = last ? rows - 1 : rows;  // slots whose next token is in the prompt
+      if (drows > 0) draft_rows(c, c->F, g.d_model, c->hist + p0 + 1, drows, p0);
+      c->nF = rows;
+    }
   }
   finish_prefill_kernel<<<1, 1, 0, c->stream>>>(c->st, c->hist, n);
   c->kv_len = n;
@@ -450,6 +575,25 @@ int ae_prefill(ae_ctx *c, const int32_t *ids, int n) {
   c->k_next = c->h_st->k_next; c->y_next = c->h_st->y_next; c->k_next_valid = true;
   c->have_pending = true;
   c->cur_k = 0;
+  return AE_OK;
+}
+
+int ae_set_prefill_mode(ae_ctx *c, int mode, int chunk_rows) {
+  if (!c) return AE_EINVAL;
+  if (mode != AE_PREFILL_AUTO && mode != AE_PREFILL_BLOCKS && mode != AE_PREFILL_DENSE)
+    return fail(c, AE_EINVAL, "ae_set_prefill_mode: unknown mode");
+  if (chunk_rows != 0 && (chunk_rows < 128 || chunk_rows > 8192 || chunk_rows % 128))
+    return fail(c, AE_EINVAL, "ae_set_prefill_mode: chunk_rows must be a multiple of 128 in [128, 8192]");
+  if (mode == AE_PREFILL_DENSE && !dense_ok(c))
+    return fail(c, AE_EUNSUPPORTED, "the dense prompt pass needs bf16 weights and d_model >= 256");
+  c->prefill_mode = mode;
+  if (chunk_rows && chunk_rows != c->dense_chunk) {
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    for (void *p : c->dense_owned) hipFree(p);
+    c->dense_owned.clear();
+    c->dense_cap = 0;
+    c->dense_chunk = chunk_rows;
+  }
   return AE_OK;
 }
 

@@ -15,6 +15,8 @@ constexpr int kMaxRows = 16;       // rows of one verify / prefill block (one MF
 constexpr int kAttnChunk = 256;    // keys per split-KV workgroup (fixed by absolute slot)
 constexpr int kMaxSplits = 64;     // n_ctx_max / kAttnChunk upper bound
 constexpr int kMaxLdlpHidden = 1024;
+constexpr int kDenseRB = 8;        // activation row-blocks per workgroup of the dense prompt GEMM (128 rows)
+constexpr int kDenseMinPrompt = 64;   // shorter prompts go through the 16-row decode kernels
 
 // Device-resident step state.  The host mirrors kv_len (it learns it at every accept).
 struct DevState {
@@ -91,6 +93,14 @@ struct ae_ctx {
   ae::DevState *st = nullptr;      // device state
   ae::DevState *h_st = nullptr;    // pinned host mirror used for read-back / uploads
   int32_t *h_ids = nullptr;        // pinned staging for ids
+
+  // dense prompt pass (bf16 only): chunk buffers, allocated at the first long prompt
+  int prefill_mode = 0;            // AE_PREFILL_AUTO / _BLOCKS / _DENSE
+  int dense_chunk = 2048;          // rows per dense pass (multiple of 128)
+  int dense_cap = 0;               // rows the buffers below hold
+  std::vector<void *> dense_owned;
+  float *px = nullptr, *pq = nullptr, *prinv = nullptr, *pssq_a = nullptr, *pssq_f = nullptr;
+  void *pxa = nullptr, *pxf = nullptr, *pxatt = nullptr, *pxh = nullptr, *pxcat = nullptr;
 
   // host-side state machine
   int kv_len = 0, dlen = 0, nF = 0;
@@ -198,5 +208,17 @@ void launch_embed_packed(const void *emb, const int32_t *ids_dev, int rows, int 
 void launch_pack_rows(const float *src, int ld, int rows, int K, const float *gain, void *Xp, hipStream_t s);
 void launch_draft_cat_packed(const float *feat, int feat_ld, const void *emb, const int32_t *next_ids, int rows, int d,
                              void *Xp, hipStream_t s);
+
+// ---- dense prompt pass (kernels_dense.hip); packed buffers hold RB row-blocks ----
+// Same GemmLaunch as the decode GEMM (rows = rows of the chunk, row0 unused); rinv != nullptr
+// folds RMSNorm in (1/rms per row from launch_rinv_finalize).
+void launch_gemm_dense(const GemmLaunch &L, int RB, const float *rinv, hipStream_t s);
+void launch_rinv_finalize(const float *ssq, int RBused, int P, int K, float eps, float *rinv, hipStream_t s);
+void launch_embed_dense(const void *emb, const int32_t *ids_dev, int rows, int d, const float *gain, float *x, void *Xp,
+                        int RB, float *ssq, hipStream_t s);
+void launch_draft_cat_dense(const float *x, int rows, int d, const float *gain, float eps, const void *emb,
+                            const int32_t *next_ids, void *Xp, int RB, hipStream_t s);
+void launch_attention_prefill(const float *q, int rows, int pos0, const ae_config &c, const void *kv_layer, size_t v_off,
+                              void *Xp_out, int RB, hipStream_t s);
 
 }  // namespace ae

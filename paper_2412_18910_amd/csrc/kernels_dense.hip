@@ -1,0 +1,363 @@
+// Dense prompt pass (first iteration of Algorithm 1 of arxiv 2412.18910 on a long prompt):
+// the only place of the method where the matrix cores, not HBM, are the limit.
+//
+// The prompt is processed in chunks of up to a few thousand rows.  Activations of a chunk
+// live in the packed bf16 hi/lo form of the decode step, extended to many row-blocks
+// (Xp[kt][rb][h][64], see packed.h); weights are the same k-major MFMA tiles the decode
+// GEMMs stream.  Kernels:
+//  * gemm_dense_kernel: workgroup tile = 256 weight rows x 128 activation rows.  Each of the
+//    4 waves owns 4 weight row-blocks (A operands loaded straight from the tiled matrix, one
+//    coalesced 1 KB burst per tile) and all 8 activation row-blocks, which the workgroup
+//    stages through double-buffered LDS (32 KB per stage of 2 k-tiles).  64 MFMAs per wave
+//    and k-tile against 16 LDS reads; epilogues are those of the decode GEMM.
+//  * attn_prefill_kernel: causal flash attention straight off the tiled KV cache; a wave owns
+//    16 (row, head) pairs of one KV head and walks the visible keys 64 at a time with an
+//    online softmax in the log2 domain; no partials, no merge, packed output.
+//  * embedding, 1/rms finalisation and the draft head's [feature ; embedding] input.
+#include "ae_internal.h"
+#include "gemm_epilogue.h"
+#include "packed.h"
+
+namespace ae {
+
+constexpr int DN = 4;    // weight row-blocks per wave
+constexpr int DM = kDenseRB;   // activation row-blocks per workgroup (128 rows)
+constexpr int DKS = 2;   // k-tiles per pipeline stage
+
+template <int EPI, bool NORM>
+__global__ __launch_bounds__(256) void gemm_dense_kernel(const GemmArgs a) {
+  extern __shared__ u32x4 bs[];   // [2][DKS][DM][2][64]
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, g = lane >> 4, m = lane & 15;
+  const int rb0 = blockIdx.y * DM;
+  if (rb0 * 16 >= a.rows) return;
+  // a workgroup hanging over the end of the matrix slides back (recomputes, stores nothing new)
+  const int nbw = min((int)blockIdx.x * (4 * DN), a.NBtot - 4 * DN) + w * DN;
+  const size_t kstride = (size_t)a.NBtot * 64, kts = (size_t)a.RB * 128;
+  const u32x4 *wp = a.W + (size_t)nbw * 64 + lane;
+  const u32x4 *xsrc = a.Xp + (size_t)rb0 * 128 + tid;   // the DM row-blocks of one k-tile: 1024 contiguous pieces
+  constexpr int STAGE = DKS * DM * 128;                 // pieces per LDS stage
+
+  f32x4 acc[DN][DM];
+#pragma unroll
+  for (int i = 0; i < DN; ++i)
+#pragma unroll
+    for (int j = 0; j < DM; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  u32x4 wa[DKS][DN], wn[DKS][DN], xs[DKS][DM / 2];
+#pragma unroll
+  for (int ks = 0; ks < DKS; ++ks) {
+#pragma unroll
+    for (int i = 0; i < DN; ++i) wa[ks][i] = wp[ks * kstride + i * 64];
+#pragma unroll
+    for (int i = 0; i < DM / 2; ++i) xs[ks][i] = xsrc[ks * kts + i * 256];
+  }
+#pragma unroll
+  for (int ks = 0; ks < DKS; ++ks)
+#pragma unroll
+    for (int i = 0; i < DM / 2; ++i) bs[ks * (DM * 128) + i * 256 + tid] = xs[ks][i];
+  __syncthreads();
+
+  const int NS = a.KT / DKS;
+  for (int st = 0; st < NS; ++st) {
+    const int cur = st & 1;
+    const size_t tn = (size_t)min(st + 1, NS - 1) * DKS;   // the last stage re-issues its own loads (ignored)
+#pragma unroll
+    for (int ks = 0; ks < DKS; ++ks) {
+#pragma unroll
+      for (int i = 0; i < DN; ++i) wn[ks][i] = wp[(tn + ks) * kstride + i * 64];
+#pragma unroll
+      for (int i = 0; i < DM / 2; ++i) xs[ks][i] = xsrc[(tn + ks) * kts + i * 256];
+    }
+    const u32x4 *bcur = bs + cur * STAGE + m * 4 + g;   // packed slot of (row m, k-octet g)
+#pragma unroll
+    for (int ks = 0; ks < DKS; ++ks) {
+#pragma unroll
+      for (int j = 0; j < DM; ++j) {
+        const u32x4 bh = bcur[(ks * DM + j) * 128], bl = bcur[(ks * DM + j) * 128 + 64];
+#pragma unroll
+        for (int i = 0; i < DN; ++i) acc[i][j] = mfma_bf16(wa[ks][i], bh, acc[i][j]);
+#pragma unroll
+        for (int i = 0; i < DN; ++i) acc[i][j] = mfma_bf16(wa[ks][i], bl, acc[i][j]);
+      }
+    }
+    u32x4 *bnext = bs + (cur ^ 1) * STAGE + tid;
+#pragma unroll
+    for (int ks = 0; ks < DKS; ++ks) {
+#pragma unroll
+      for (int i = 0; i < DM / 2; ++i) bnext[ks * (DM * 128) + i * 256] = xs[ks][i];
+#pragma unroll
+      for (int i = 0; i < DN; ++i) wa[ks][i] = wn[ks][i];
+    }
+    __syncthreads();
+  }
+
+  constexpr int STEP = EPI == EPI_SWIGLU ? 2 : 1;
+#pragma unroll
+  for (int i = 0; i < DN; i += STEP) {
+    const int nb = nbw + i;
+    if (nb < (int)blockIdx.x * (4 * DN)) continue;   // slid-back duplicate of a neighbour's row-block
+#pragma unroll
+    for (int j = 0; j < DM; ++j) {
+      const int rb = rb0 + j, row = rb * 16 + m;
+      const bool row_ok = row < a.rows;
+      const float rinv = NORM ? a.rinv[row] : 1.f;
+      epi_tile<EPI>(a, acc[i][j], acc[i + STEP - 1][j], nb, g, m, rb, row_ok, rinv, kts);
+    }
+  }
+}
+
+template <int EPI, bool NORM>
+static void launch_dense_cfg(const GemmArgs &a, hipStream_t s) {
+  constexpr int sm = 2 * DKS * DM * 128 * 16;
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void *)gemm_dense_kernel<EPI, NORM>, hipFuncAttributeMaxDynamicSharedMemorySize, sm);
+    attr_set = true;
+  }
+  const dim3 grid((a.NBtot + 4 * DN - 1) / (4 * DN), (a.rows + DM * 16 - 1) / (DM * 16));
+  gemm_dense_kernel<EPI, NORM><<<grid, 256, sm, s>>>(a);
+}
+
+void launch_gemm_dense(const GemmLaunch &L, int RB, const float *rinv, hipStream_t s) {
+  GemmArgs a{};
+  a.W = (const u32x4 *)L.W->tiled;
+  a.NBtot = L.W->N / 16;
+  a.KT = L.W->K / 32;
+  a.Xp = (const u32x4 *)L.Xp;
+  a.rows = L.rows;
+  a.RB = RB;
+  a.rinv = rinv;
+  a.bias = L.bias;
+  a.Xp_out = (u32x4 *)L.Xp_out; a.gain_out = L.gain_out; a.ssq_out = L.ssq_out;
+  int end = 0;
+  for (int i = 0; i < 3; ++i) {
+    if (i < L.nseg) end += L.seg_N[i] / 16;
+    a.seg[i] = GemmSeg{i < L.nseg ? L.Y[i] : nullptr, i < L.nseg ? L.ldy[i] : 0, i < L.nseg ? end : 0x7fffffff};
+  }
+  a.rope_tab = L.rope_tab; a.Kc = (uint16_t *)L.Kc; a.Vc = (uint16_t *)L.Vc;
+  a.pos0 = L.pos0; a.n_ctx = L.n_ctx; a.hd = L.hd;
+  const bool norm = rinv != nullptr;
+  if (L.epi == EPI_QKV) launch_dense_cfg<EPI_QKV, true>(a, s);
+  else if (L.epi == EPI_SWIGLU) launch_dense_cfg<EPI_SWIGLU, true>(a, s);
+  else if (L.epi == EPI_RESID) launch_dense_cfg<EPI_RESID, false>(a, s);
+  else if (norm) launch_dense_cfg<EPI_STORE, true>(a, s);
+  else launch_dense_cfg<EPI_STORE, false>(a, s);
+}
+
+// ------------------------------------------------------------------ 1/rms of every row
+// ssq: [RB][P][16] partial sums of x^2 -> rinv[rb*16 + m]; one workgroup per row-block,
+// 16 threads per row, fixed summation order.
+__global__ __launch_bounds__(256) void rinv_finalize_kernel(const float *ssq, int P, int K, float eps, float *rinv) {
+  __shared__ float sh[256];
+  const int rb = blockIdx.x, m = threadIdx.x & 15, pg = threadIdx.x >> 4;
+  float t = 0.f;
+  for (int p = pg; p < P; p += 16) t += ssq[((size_t)rb * P + p) * 16 + m];
+  sh[threadIdx.x] = t;
+  __syncthreads();
+  if (threadIdx.x < 16) {
+    float tot = 0.f;
+    for (int i = 0; i < 16; ++i) tot += sh[i * 16 + threadIdx.x];
+    rinv[rb * 16 + threadIdx.x] = 1.0f / sqrtf(tot / (float)K + eps);
+  }
+}
+
+void launch_rinv_finalize(const float *ssq, int RBused, int P, int K, float eps, float *rinv, hipStream_t s) {
+  rinv_finalize_kernel<<<RBused, 256, 0, s>>>(ssq, P, K, eps, rinv);
+}
+
+// ------------------------------------------------------------------ packed-form producers
+// Embedding rows -> float residual stream, packed(x * gain) and the row's sum of x^2 ([rb][1][16]).
+__global__ __launch_bounds__(256) void embed_dense_kernel(const uint16_t *emb, const int32_t *ids, int d, const float *gain,
+                                                          float *x, u32x4 *Xp, size_t kts, float *ssq) {
+  __shared__ float red[4];
+  const int r = blockIdx.x, rb = r >> 4, m = r & 15;
+  const uint16_t *src = emb + (size_t)ids[r] * d;
+  u32x4 *xp = Xp + (size_t)rb * 128;
+  float ss = 0.f;
+  for (int k0 = threadIdx.x * 4; k0 < d; k0 += 1024) {
+    const uint2 raw = *reinterpret_cast<const uint2 *>(src + k0);
+    const float v0 = __uint_as_float(raw.x << 16), v1 = __uint_as_float(raw.x & 0xffff0000u);
+    const float v2 = __uint_as_float(raw.y << 16), v3 = __uint_as_float(raw.y & 0xffff0000u);
+    *reinterpret_cast<float4 *>(x + (size_t)r * d + k0) = make_float4(v0, v1, v2, v3);
+    ss += v0 * v0 + v1 * v1 + v2 * v2 + v3 * v3;
+    const float4 gn = *reinterpret_cast<const float4 *>(gain + k0);
+    packed_store4(xp, m, k0, v0 * gn.x, v1 * gn.y, v2 * gn.z, v3 * gn.w, kts);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  if (threadIdx.x == 0) ssq[r] = (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+void launch_embed_dense(const void *emb, const int32_t *ids_dev, int rows, int d, const float *gain, float *x, void *Xp,
+                        int RB, float *ssq, hipStream_t s) {
+  embed_dense_kernel<<<rows, 256, 0, s>>>((const uint16_t *)emb, ids_dev, d, gain, x, (u32x4 *)Xp, (size_t)RB * 128, ssq);
+}
+
+// Draft head input of every slot of the chunk whose next token is known (Eq. 2):
+// [RMSNorm(x_r) * gain ; embedding of the following token] -> packed, K = 2d.
+__global__ __launch_bounds__(256) void draft_cat_dense_kernel(const float *x, int d, const float *gain, float eps,
+                                                              const uint16_t *emb, const int32_t *next_ids, u32x4 *Xp,
+                                                              size_t kts) {
+  __shared__ float red[4];
+  const int r = blockIdx.x, rb = r >> 4, m = r & 15;
+  const float *xr = x + (size_t)r * d;
+  float ss = 0.f;
+  for (int k0 = threadIdx.x * 4; k0 < d; k0 += 1024) {
+    const float4 v = *reinterpret_cast<const float4 *>(xr + k0);
+    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  const float rinv = 1.0f / sqrtf(((red[0] + red[1]) + (red[2] + red[3])) / (float)d + eps);
+  u32x4 *xp = Xp + (size_t)rb * 128;
+  const uint16_t *e = emb + (size_t)next_ids[r] * d;
+  for (int k0 = threadIdx.x * 4; k0 < d; k0 += 1024) {
+    const float4 v = *reinterpret_cast<const float4 *>(xr + k0);
+    const float4 gn = *reinterpret_cast<const float4 *>(gain + k0);
+    packed_store4(xp, m, k0, v.x * rinv * gn.x, v.y * rinv * gn.y, v.z * rinv * gn.z, v.w * rinv * gn.w, kts);
+    const uint2 raw = *reinterpret_cast<const uint2 *>(e + k0);
+    packed_store4(xp, m, d + k0, __uint_as_float(raw.x << 16), __uint_as_float(raw.x & 0xffff0000u),
+                  __uint_as_float(raw.y << 16), __uint_as_float(raw.y & 0xffff0000u), kts);
+  }
+}
+
+void launch_draft_cat_dense(const float *x, int rows, int d, const float *gain, float eps, const void *emb,
+                            const int32_t *next_ids, void *Xp, int RB, hipStream_t s) {
+  draft_cat_dense_kernel<<<rows, 256, 0, s>>>(x, d, gain, eps, (const uint16_t *)emb, next_ids, (u32x4 *)Xp, (size_t)RB * 128);
+}
+
+// ------------------------------------------------------------------ causal attention of a prompt chunk
+// q: float [rows][H*HD] of the chunk (already rotated); chunk row i sits at slot pos0 + i and
+// sees slots 0..pos0+i of the tiled cache (which already holds the chunk's own K and V).
+// Pairs (row, query head of the KV head's group) are numbered r = row*G + head%G; a wave owns
+// 16 consecutive pairs, a workgroup 64; late (long) tiles are scheduled first.
+template <int HD>
+__global__ __launch_bounds__(256) void attn_prefill_kernel(const float *q, int rows, int pos0, int H, int Hkv, int n_ctx,
+                                                           const u32x4 *Kc, const u32x4 *Vc, u32x4 *Xp_out, size_t kts,
+                                                           float scale_log2e) {
+  constexpr int DT = HD / 32, VT = HD / 16;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 4, m = lane & 15;
+  const int kh = blockIdx.x, G = H / Hkv, R = rows * G;
+  const int r0 = (((int)gridDim.y - 1 - (int)blockIdx.y) * 4 + w) * 16;
+  if (r0 >= R) return;   // wave-uniform; the kernel has no barriers
+  const int r = r0 + m;
+  const bool rok = r < R;
+  const int rr = rok ? r : R - 1;
+  const int row = rr / G, head = kh * G + rr % G;
+  const int limit = pos0 + row;                          // last slot this lane's row may see
+  const int last_key = pos0 + min(r0 + 15, R - 1) / G;   // last slot any row of the tile sees
+
+  u32x4 qh[DT], ql[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) {
+    const float *src = q + ((size_t)row * H + head) * HD + dt * 32 + g * 8;
+    const float4 a = *reinterpret_cast<const float4 *>(src), b = *reinterpret_cast<const float4 *>(src + 4);
+    uint32_t h0, h1, h2, h3, l0, l1, l2, l3;
+    split2(a.x * scale_log2e, a.y * scale_log2e, h0, l0);
+    split2(a.z * scale_log2e, a.w * scale_log2e, h1, l1);
+    split2(b.x * scale_log2e, b.y * scale_log2e, h2, l2);
+    split2(b.z * scale_log2e, b.w * scale_log2e, h3, l3);
+    qh[dt] = u32x4{h0, h1, h2, h3};
+    ql[dt] = u32x4{l0, l1, l2, l3};
+  }
+
+  float mx = -INFINITY, lsum = 0.f;
+  f32x4 O[VT];
+#pragma unroll
+  for (int dt = 0; dt < VT; ++dt) O[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  for (int kb = 0; kb <= last_key; kb += 64) {
+    u32x4 kreg[4][DT], vreg[2][VT];
+    const u32x4 *kp = Kc + (((size_t)kh * (n_ctx / 16) + (kb >> 4)) * DT) * 64 + lane;
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) kreg[kt][dt] = kp[(kt * DT + dt) * 64];
+    const u32x4 *vp = Vc + (((size_t)kh * (n_ctx / 32) + (kb >> 5)) * VT) * 64 + lane;
+#pragma unroll
+    for (int vb = 0; vb < 2; ++vb)
+#pragma unroll
+      for (int dt = 0; dt < VT; ++dt) vreg[vb][dt] = vp[(vb * VT + dt) * 64];
+
+    f32x4 S[4];
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt) S[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+#pragma unroll
+      for (int kt = 0; kt < 4; ++kt) S[kt] = mfma_bf16(kreg[kt][dt], qh[dt], S[kt]);
+#pragma unroll
+      for (int kt = 0; kt < 4; ++kt) S[kt] = mfma_bf16(kreg[kt][dt], ql[dt], S[kt]);
+    }
+    float bmax = -INFINITY;
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int key = kb + kt * 16 + 4 * g + e;
+        S[kt][e] = key <= limit ? S[kt][e] : -INFINITY;
+        bmax = fmaxf(bmax, S[kt][e]);
+      }
+    bmax = fmaxf(bmax, __shfl_xor(bmax, 16, 64));
+    bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
+    const float mnew = fmaxf(mx, bmax);   // finite from the first block on: slot 0 is visible to every row
+    const float alpha = __builtin_amdgcn_exp2f(mx - mnew);
+    float bsum = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        S[kt][e] = __builtin_amdgcn_exp2f(S[kt][e] - mnew);
+        bsum += S[kt][e];
+      }
+    bsum += __shfl_xor(bsum, 16, 64);
+    bsum += __shfl_xor(bsum, 32, 64);
+    lsum = lsum * alpha + bsum;
+    mx = mnew;
+#pragma unroll
+    for (int dt = 0; dt < VT; ++dt) O[dt] *= alpha;
+    // P^T as B operand: k-slot e of lane group g = key 16*(e/4) + 4g + e%4 of a 32-key block
+#pragma unroll
+    for (int vb = 0; vb < 2; ++vb) {
+      uint32_t h0, h1, h2, h3, l0, l1, l2, l3;
+      split2(S[2 * vb][0], S[2 * vb][1], h0, l0);
+      split2(S[2 * vb][2], S[2 * vb][3], h1, l1);
+      split2(S[2 * vb + 1][0], S[2 * vb + 1][1], h2, l2);
+      split2(S[2 * vb + 1][2], S[2 * vb + 1][3], h3, l3);
+      const u32x4 ph = {h0, h1, h2, h3}, pl = {l0, l1, l2, l3};
+#pragma unroll
+      for (int dt = 0; dt < VT; ++dt) O[dt] = mfma_bf16(vreg[vb][dt], ph, O[dt]);
+#pragma unroll
+      for (int dt = 0; dt < VT; ++dt) O[dt] = mfma_bf16(vreg[vb][dt], pl, O[dt]);
+    }
+  }
+  if (rok) {
+    const float inv = 1.0f / lsum;
+    u32x4 *xp = Xp_out + (size_t)(row >> 4) * 128;
+#pragma unroll
+    for (int dt = 0; dt < VT; ++dt)
+      packed_store4(xp, row & 15, head * HD + dt * 16 + 4 * g, O[dt][0] * inv, O[dt][1] * inv, O[dt][2] * inv,
+                    O[dt][3] * inv, kts);
+  }
+}
+
+void launch_attention_prefill(const float *q, int rows, int pos0, const ae_config &c, const void *kv_layer, size_t v_off,
+                              void *Xp_out, int RB, hipStream_t s) {
+  const int G = c.n_heads / c.n_kv_heads, R = rows * G, HD = c.head_dim;
+  const dim3 grid(c.n_kv_heads, (R + 63) / 64);
+  const float scale_log2e = 1.4426950408889634f / sqrtf((float)HD);
+  const u32x4 *Kc = (const u32x4 *)kv_layer, *Vc = (const u32x4 *)((const char *)kv_layer + v_off);
+  const int cap = kv_capacity(c);
+  if (HD == 128)
+    attn_prefill_kernel<128><<<grid, 256, 0, s>>>(q, rows, pos0, c.n_heads, c.n_kv_heads, cap, Kc, Vc, (u32x4 *)Xp_out,
+                                                 (size_t)RB * 128, scale_log2e);
+  else
+    attn_prefill_kernel<64><<<grid, 256, 0, s>>>(q, rows, pos0, c.n_heads, c.n_kv_heads, cap, Kc, Vc, (u32x4 *)Xp_out,
+                                                (size_t)RB * 128, scale_log2e);
+}
+
+}  // namespace ae

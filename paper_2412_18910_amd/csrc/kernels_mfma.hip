@@ -26,6 +26,7 @@
 //    tiles interleaved in the matrix), each optionally emitting the packed form (and the
 //    x^2 partials) for the next GEMM.
 #include "ae_internal.h"
+#include "gemm_epilogue.h"
 #include "packed.h"
 
 namespace ae {
@@ -60,40 +61,6 @@ void launch_retile(const void *rowmajor, int N, int K, void *tiled, int NBtot, i
 }
 
 // ------------------------------------------------------------------ GEMM
-__device__ __forceinline__ float silu_dev(float x) { return x / (1.0f + expf(-x)); }
-
-struct GemmSeg {
-  float *Y;     // float destination of this range of row-blocks
-  int ldy;
-  int nb_end;   // exclusive end of the range in fused row-block indices
-};
-
-struct GemmArgs {
-  const u32x4 *W;       // fused k-major tiled matrix
-  const u32x4 *Xp;      // packed activations [KT][2][64]
-  const float *ssq_in;  // NORM: [P_in][16] partial sums of x^2
-  const float *bias;    // [N] or nullptr (EPI_STORE, segment 0)
-  u32x4 *Xp_out;        // packed output for the next GEMM (nullable)
-  const float *gain_out;  // gain folded into Xp_out (nullable = 1)
-  float *ssq_out;       // [NBtot][16] partial sums of the new x^2 (nullable)
-  GemmSeg seg[3];
-  int NBtot, KT, rows, row0, P_in;   // output row m reads packed row row0 + m
-  float eps;
-  float *amax_val;      // EPI_STORE, LM head: per row-block, per row maximum of the outputs ...
-  int32_t *amax_idx;    // ... and the lowest column index attaining it ([NBtot][16] each)
-  // EPI_QKV: rotary embedding + KV-cache append in the epilogue
-  const float2 *rope_tab;   // [slot][hd/2] (cos, sin)
-  uint16_t *Kc, *Vc;        // this layer's tiled bf16 cache (layouts of kernels_attn_mfma.hip)
-  int pos0, n_ctx, hd;
-};
-
-__device__ __forceinline__ uint16_t f2bf_rne(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7f800000u) == 0x7f800000u) return (uint16_t)(u >> 16);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
-
 template <int EPI, bool NORM, int NACC, int NW, int D>
 __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(const GemmArgs a) {
   __shared__ f32x4 red[NW][NACC][64];
@@ -184,110 +151,13 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(const GemmArgs a) {
     f32x4 s = red[0][rb][lane];
 #pragma unroll
     for (int ww = 1; ww < NW; ++ww) s += red[ww][rb][lane];
+    f32x4 u = s;
     if (EPI == EPI_SWIGLU) {
-      // fused matrix interleaves gate (even row-blocks) and up (odd): h = silu(gate) * up
-      f32x4 u = red[0][rb + 1][lane];
+      u = red[0][rb + 1][lane];
 #pragma unroll
       for (int ww = 1; ww < NW; ++ww) u += red[ww][rb + 1][lane];
-      if (row_ok) {
-        const int n = (nb >> 1) * 16 + g * 4;
-        packed_store4(a.Xp_out, m, n, silu_dev(s[0] * rinv) * (u[0] * rinv), silu_dev(s[1] * rinv) * (u[1] * rinv),
-                      silu_dev(s[2] * rinv) * (u[2] * rinv), silu_dev(s[3] * rinv) * (u[3] * rinv));
-      }
-    } else if (EPI == EPI_QKV) {
-      // Row-blocks [0, seg0) = q, [seg0, seg1) = k (both with the rotary row order of
-      // retile_kernel), [seg1, ..) = v.  q: rotate, store float in natural column order.
-      // k: rotate, round to bf16, append to the tiled K cache.  v: round, append.
-      int si = 0, nbs = nb;
-      if (nb >= a.seg[0].nb_end) { si = 1; nbs = nb - a.seg[0].nb_end; }
-      if (nb >= a.seg[1].nb_end) { si = 2; nbs = nb - a.seg[1].nb_end; }
-      const int hd = a.hd, bph = hd >> 4, head = nbs / bph, j = nbs % bph;
-      const int slot = a.pos0 + (row_ok ? m : 0);
-      float4 o = make_float4(s[0] * rinv, s[1] * rinv, s[2] * rinv, s[3] * rinv);
-      if (si < 2) {
-        const int i0 = 8 * j + 4 * (g & 1);   // rotary index of the pair, first-half coordinates
-        const float4 cs01 = *reinterpret_cast<const float4 *>(a.rope_tab + (size_t)slot * (hd >> 1) + i0);
-        const float4 cs23 = *reinterpret_cast<const float4 *>(a.rope_tab + (size_t)slot * (hd >> 1) + i0 + 2);
-        const float sgn = g < 2 ? -1.f : 1.f;   // first half: a*c - b*s; second half: b*c + a*s
-        const float p0 = __shfl_xor(o.x, 32, 64), p1 = __shfl_xor(o.y, 32, 64);
-        const float p2 = __shfl_xor(o.z, 32, 64), p3 = __shfl_xor(o.w, 32, 64);
-        o.x = o.x * cs01.x + sgn * p0 * cs01.y;
-        o.y = o.y * cs01.z + sgn * p1 * cs01.w;
-        o.z = o.z * cs23.x + sgn * p2 * cs23.y;
-        o.w = o.w * cs23.z + sgn * p3 * cs23.w;
-        const int dcol = (g < 2 ? 0 : hd >> 1) + i0;   // natural head-dim index of o.x
-        if (row_ok) {
-          if (si == 0) {
-            *reinterpret_cast<float4 *>(a.seg[0].Y + (size_t)m * a.seg[0].ldy + head * hd + dcol) = o;
-          } else {
-            // K tile layout: [kh][slot/16][d/32][lane = ((d%32)/8)*16 + slot%16][d%8]
-            const size_t idx = ((((size_t)head * (a.n_ctx >> 4) + (slot >> 4)) * (hd >> 5) + (dcol >> 5)) * 64 +
-                                ((dcol & 31) >> 3) * 16 + (slot & 15)) * 8 + (dcol & 7);
-            u32x2 pk;
-            pk[0] = (uint32_t)f2bf_rne(o.x) | ((uint32_t)f2bf_rne(o.y) << 16);
-            pk[1] = (uint32_t)f2bf_rne(o.z) | ((uint32_t)f2bf_rne(o.w) << 16);
-            *reinterpret_cast<u32x2 *>(a.Kc + idx) = pk;
-          }
-        }
-      } else if (row_ok) {
-        // V tile layout: [kh][slot/32][d/16][lane = ((slot%16)/4)*16 + d%16][e = slot%4 + 4*((slot%32)/16)]
-        const int w16 = slot & 15, e = (w16 & 3) + 4 * ((slot & 31) >> 4);
-        const size_t base = ((((size_t)head * (a.n_ctx >> 5) + (slot >> 5)) * bph + j) * 64 + (w16 >> 2) * 16 + g * 4) * 8 + e;
-        a.Vc[base] = f2bf_rne(o.x);
-        a.Vc[base + 8] = f2bf_rne(o.y);
-        a.Vc[base + 16] = f2bf_rne(o.z);
-        a.Vc[base + 24] = f2bf_rne(o.w);
-      }
-    } else {
-      int si = 0, nbs = nb;
-      if (nb >= a.seg[0].nb_end) { si = 1; nbs = nb - a.seg[0].nb_end; }
-      if (nb >= a.seg[1].nb_end) { si = 2; nbs = nb - a.seg[1].nb_end; }
-      const int n = nbs * 16 + g * 4;   // this lane holds columns n..n+3 of row m
-      float4 o = make_float4(s[0] * rinv, s[1] * rinv, s[2] * rinv, s[3] * rinv);
-      float ssq = 0.f;
-      if (row_ok) {
-        float *yp = a.seg[si].Y + (size_t)m * a.seg[si].ldy + n;
-        if (a.bias && si == 0) {
-          const float4 b = *reinterpret_cast<const float4 *>(a.bias + n);
-          o.x += b.x; o.y += b.y; o.z += b.z; o.w += b.w;
-        }
-        if (EPI == EPI_RESID) {
-          const float4 old = *reinterpret_cast<const float4 *>(yp);
-          o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w;
-        }
-        *reinterpret_cast<float4 *>(yp) = o;
-        if (EPI == EPI_STORE && a.amax_val) {
-          // argmax partial of this row-block: columns ascend with (g, component), ties keep the lowest
-          float bv = o.x; int bi = n;
-          if (o.y > bv) { bv = o.y; bi = n + 1; }
-          if (o.z > bv) { bv = o.z; bi = n + 2; }
-          if (o.w > bv) { bv = o.w; bi = n + 3; }
-          ssq = bv;               // reuse the two registers for the cross-lane step below
-          nbs = bi;
-        }
-        if (a.Xp_out) {
-          ssq = o.x * o.x + o.y * o.y + o.z * o.z + o.w * o.w;
-          float4 gn = make_float4(1.f, 1.f, 1.f, 1.f);
-          if (a.gain_out) gn = *reinterpret_cast<const float4 *>(a.gain_out + n);
-          packed_store4(a.Xp_out, m, n, o.x * gn.x, o.y * gn.y, o.z * gn.z, o.w * gn.w);
-        }
-      }
-      if (EPI == EPI_STORE && a.amax_val) {
-        float bv = row_ok ? ssq : -INFINITY;
-        int bi = row_ok ? nbs : 0x7fffffff;
-#pragma unroll
-        for (int o2 = 16; o2 < 64; o2 <<= 1) {
-          const float ov = __shfl_xor(bv, o2, 64);
-          const int oi = __shfl_xor(bi, o2, 64);
-          if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-        }
-        if (g == 0) { a.amax_val[nb * 16 + m] = bv; a.amax_idx[nb * 16 + m] = bi; }
-      } else if (a.ssq_out) {   // partial sum of x^2 over this row-block's 16 columns
-        ssq += __shfl_xor(ssq, 16, 64);
-        ssq += __shfl_xor(ssq, 32, 64);
-        if (g == 0) a.ssq_out[nb * 16 + m] = ssq;
-      }
     }
+    epi_tile<EPI>(a, s, u, nb, g, m, 0, row_ok, rinv, 128);
   }
 }
 
@@ -321,6 +191,7 @@ void launch_gemm_mfma(const GemmLaunch &L, hipStream_t s) {
   a.Xp = (const u32x4 *)L.Xp;
   a.rows = L.rows;
   a.row0 = L.row0;
+  a.RB = 1;
   a.ssq_in = L.ssq_in; a.P_in = L.P_in; a.eps = L.eps;
   a.bias = L.bias;
   a.Xp_out = (u32x4 *)L.Xp_out; a.gain_out = L.gain_out; a.ssq_out = L.ssq_out;

@@ -4,6 +4,9 @@
 //   k = kt*32 + (slot%4)*8 .. +7 of that row.  MFMA lane (k-octet g, row m) reads slot m*4+g:
 //   the rows of a tile are contiguous (64 bytes each), so a block of r rows touches only
 //   ceil(r/2) cache lines per tile.
+// The decode step has one block of 16 rows (k-tile stride 128 pieces).  The dense prompt
+// pass keeps RB row-blocks side by side, Xp[kt][rb][h][slot] (k-tile stride RB*128), so the
+// row-blocks a workgroup multiplies are contiguous for every k-tile.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -28,14 +31,16 @@ __device__ __forceinline__ void split2(float x0, float x1, uint32_t &hi, uint32_
   lo = __builtin_bit_cast(uint32_t, l);
 }
 
-// Store 4 consecutive k-values (k0 % 4 == 0) of row m into a packed activation buffer.
-__device__ __forceinline__ void packed_store4(u32x4 *Xp, int m, int k0, float a, float b, float c, float d) {
+// Store 4 consecutive k-values (k0 % 4 == 0) of row m (0..15) of one row-block into a packed
+// activation buffer; Xp points at the row-block's first tile, kts = k-tile stride in pieces.
+__device__ __forceinline__ void packed_store4(u32x4 *Xp, int m, int k0, float a, float b, float c, float d,
+                                              size_t kts = 128) {
   uint32_t h0, l0, h1, l1;
   split2(a, b, h0, l0);
   split2(c, d, h1, l1);
   const int kt = k0 >> 5, g = (k0 & 31) >> 3, half = (k0 & 7) >> 2;
-  u32x2 *ph = reinterpret_cast<u32x2 *>(Xp + ((size_t)kt * 2 + 0) * 64 + m * 4 + g) + half;
-  u32x2 *pl = reinterpret_cast<u32x2 *>(Xp + ((size_t)kt * 2 + 1) * 64 + m * 4 + g) + half;
+  u32x2 *ph = reinterpret_cast<u32x2 *>(Xp + (size_t)kt * kts + m * 4 + g) + half;
+  u32x2 *pl = reinterpret_cast<u32x2 *>(Xp + (size_t)kt * kts + 64 + m * 4 + g) + half;
   *ph = u32x2{h0, h1};
   *pl = u32x2{l0, l1};
 }
