@@ -48,6 +48,7 @@ def main():
     ap.add_argument("--context", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--no-prefill", action="store_true", help="skip the prompt-pass timing")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run 4 plain device copies of 512 MiB (counter calibration under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -151,6 +152,34 @@ def main():
             vb, _ = verify_bytes(cfg, 1024)
             sweep[str(m)] = {"us": round(us, 1), "GBps": round(vb / us / 1e3, 1), "frac_of_8TBps": round(vb / us / 1e3 / 8000, 3)}
 
+    # ---- prompt pass (Alg. 1, first iteration): dense chunk kernels vs 16-row blocks through the decode kernels
+    prefill = None
+    if not args.no_prefill:
+        def time_prefill(mode, reps):
+            eng.set_prefill_mode(mode)
+            eng.prefill(ctx_ids)
+            sync(); t0 = time.perf_counter()
+            for _ in range(reps):
+                eng.prefill(ctx_ids)
+            sync()
+            return (time.perf_counter() - t0) / reps * 1e3
+        dense_ms = time_prefill(Engine.PREFILL_DENSE, 3)
+        blocks_ms = time_prefill(Engine.PREFILL_BLOCKS, 1)
+        eng.set_prefill_mode(Engine.PREFILL_AUTO)
+        d, f, L = cfg.d_model, cfg.d_ffn, cfg.n_layers
+        dq, dkv = cfg.n_heads * cfg.head_dim, cfg.d_kv
+        n = args.context
+        gemm_flops = 2 * n * (L * (2 * d * dq + 2 * d * dkv + 3 * d * f) + (2 * d * d + d * (dq + 2 * dkv)))
+        attn_flops = 4 * L * dq * n * (n + 1) // 2
+        # every product runs twice on the matrix cores (bf16 hi and lo halves of the activations)
+        mfma_tflops = 2 * (gemm_flops + attn_flops) / (dense_ms * 1e-3) / 1e12
+        prefill = {"tokens": n, "dense_ms": round(dense_ms, 2), "dense_tokens_per_s": round(n / dense_ms * 1e3, 1),
+                   "blocks_ms": round(blocks_ms, 2), "speedup": round(blocks_ms / dense_ms, 2),
+                   "model_tflops": round((gemm_flops + attn_flops) / (dense_ms * 1e-3) / 1e12, 1),
+                   "roofline": {"bound": "mfma", "achieved": round(mfma_tflops, 1), "peak": 2500.0, "unit": "TFLOP/s",
+                                "frac": round(mfma_tflops / 2500.0, 4),
+                                "note": "whole prompt pass; issued bf16 MFMA flops = 2 x model flops (hi/lo split)"}}
+
     out = {
         "metric": "adaeagle_decode_tokens_per_s_7b_bs1", "value": round(tok_s, 2), "unit": "tokens/s",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 4),
@@ -165,6 +194,7 @@ def main():
         "verify": {"us": round(verify_us, 1), "bytes": vbytes, "GBps": round(verify_gbps, 1),
                    "frac_of_8TBps": round(verify_gbps / 8000, 3)},
         "verify_sweep_n1024": sweep,
+        "prefill": prefill,
         "roofline": {"bound": "hbm", "kernel": "gemm_mfma_kernel<EPI_SWIGLU, norm> (fused RMSNorm + gate/up + SwiGLU)",
                      "achieved": round(achieved, 1), "peak": 8000.0, "unit": "GB/s", "frac": round(achieved / 8000.0, 4),
                      "bytes_per_launch": gate_up_bytes, "avg_launch_us": round(kern_us, 2), "launches": kt_n,

@@ -1,24 +1,44 @@
-"""Builds libadaeagle.so (HIP, gfx950) in-tree with hipcc."""
+"""Builds libadaeagle.so (HIP, gfx950) in-tree with hipcc: one object per source, then a link."""
 import glob
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libadaeagle.so")
+OBJ_DIR = os.path.join(HERE, "_build")
+
+COMMON = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
+          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+          "-Wno-unused-result", "-Wno-unused-value",
+          "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc")]
+# Per-source additions.  The dense prompt GEMM keeps 128 accumulator registers per lane; with
+# the MFMA results allocated in ordinary VGPRs the compiler needs no accumulator-file copies
+# in its loop and the kernel fits 2 waves per SIMD.
+EXTRA = {"kernels_dense.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def sources():
     return sorted(glob.glob(os.path.join(HERE, "csrc", "*.hip")))
 
 
+def _compile(src, verbose):
+    obj = os.path.join(OBJ_DIR, os.path.basename(src)[:-4] + ".o")
+    cmd = ["hipcc", "-c"] + COMMON + EXTRA.get(os.path.basename(src), []) + ["-o", obj, src]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    return obj
+
+
 def build(verbose=False):
     """Compile every HIP source for gfx950 and link the shared library."""
-    cmd = ["hipcc", "-O3", "-std=c++17", "--offload-arch=gfx950", "-shared", "-fPIC",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wno-unused-result", "-Wno-unused-value", "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc"),
-           "-o", LIB] + sources()
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
+        objs = list(ex.map(lambda s: _compile(s, verbose), sources()))
+    cmd = ["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)

@@ -28,6 +28,7 @@ struct GemmArgs {
   GemmSeg seg[3];
   int NBtot, KT, rows, row0, P_in;   // output row m reads packed row row0 + m (decode)
   int RB;               // row-blocks held by the packed buffers (decode: 1)
+  int w_bytes, xp_bytes;  // dense: sizes of W and Xp (buffer-load range checks)
   float eps;
   float *amax_val;      // EPI_STORE, LM head: per row-block, per row maximum of the outputs ...
   int32_t *amax_idx;    // ... and the lowest column index attaining it ([NBtot][16] each)

@@ -21,20 +21,50 @@
 namespace ae {
 
 constexpr int DN = 4;    // weight row-blocks per wave
-constexpr int DM = kDenseRB;   // activation row-blocks per workgroup (128 rows)
 constexpr int DKS = 2;   // k-tiles per pipeline stage
 
-template <int EPI, bool NORM>
-__global__ __launch_bounds__(256) void gemm_dense_kernel(const GemmArgs a) {
+// DM = activation row-blocks per workgroup: 8 (128 rows), or 4 when the wide tile would leave
+// compute units without two resident workgroups.
+template <int EPI, bool NORM, int DM>
+__global__ __launch_bounds__(256, 2) void gemm_dense_kernel(const GemmArgs a) {
   extern __shared__ u32x4 bs[];   // [2][DKS][DM][2][64]
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, g = lane >> 4, m = lane & 15;
-  const int rb0 = blockIdx.y * DM;
-  if (rb0 * 16 >= a.rows) return;
+  const int tid = threadIdx.x, lane = tid & 63, g = lane >> 4, m = lane & 15;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps operand bases in scalar registers
+  // Workgroup -> tile.  Workgroups are handed to the 8 XCDs round-robin (id % 8) and each XCD
+  // has its own L2, so XCD x takes a contiguous share of the tile list, and the list runs
+  // through panels of 8 weight tiles with the activation tile advancing every 8 entries: the
+  // ~64 workgroups resident on an XCD then cover about 8 x 8 tiles and share their operands in
+  // that L2 (measured: 3.3 GB -> see the design notes of HBM traffic per 7B gate/up GEMM).
+  const int NT = (a.NBtot + 4 * DN - 1) / (4 * DN), MT = (a.rows + DM * 16 - 1) / (DM * 16);
+  const int per = (NT * MT + 7) >> 3;
+  const int v = ((int)blockIdx.x & 7) * per + ((int)blockIdx.x >> 3);
+  if (v >= NT * MT) return;
+  constexpr int PN = 8;
+  const int full = (NT / PN) * PN * MT;
+  int tn, tm;
+  if (v < full) {
+    const int r = v % (PN * MT);
+    tn = (v / (PN * MT)) * PN + r % PN;
+    tm = r / PN;
+  } else {
+    const int r = v - full, pn = NT % PN;
+    tn = (NT / PN) * PN + r % pn;
+    tm = r / pn;
+  }
+  const int rb0 = tm * DM;
   // a workgroup hanging over the end of the matrix slides back (recomputes, stores nothing new)
-  const int nbw = min((int)blockIdx.x * (4 * DN), a.NBtot - 4 * DN) + w * DN;
-  const size_t kstride = (size_t)a.NBtot * 64, kts = (size_t)a.RB * 128;
-  const u32x4 *wp = a.W + (size_t)nbw * 64 + lane;
-  const u32x4 *xsrc = a.Xp + (size_t)rb0 * 128 + tid;   // the DM row-blocks of one k-tile: 1024 contiguous pieces
+  const int nbw = min(tn * (4 * DN), a.NBtot - 4 * DN) + w * DN;
+  const size_t kts = (size_t)a.RB * 128;
+  // Operands come through buffer loads: resource descriptor and per-stage byte offset in
+  // scalar registers, one fixed per-lane offset register each (out-of-range reads return 0).
+  // The DM row-blocks of one k-tile are 1024 contiguous pieces (16 tiles of 64); a thread
+  // fetches the piece its MFMA lane position needs (packed slot m*4+g of tile w + 4i), so LDS
+  // holds the tiles in lane order and its accesses are conflict-free.
+  const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc((void *)a.W, 0, a.w_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc((void *)a.Xp, 0, a.xp_bytes, 0x00020000);
+  const unsigned wl = lane * 16, xl = (m * 4 + g) * 16;                  // per-lane byte offsets
+  const unsigned kstride_b = a.NBtot * 1024u, kts_b = a.RB * 2048u;      // bytes per k-tile
+  unsigned wq = nbw * 1024u, xq = (rb0 * 128u + w * 64u) * 16u;           // stage to load next (uniform)
   constexpr int STAGE = DKS * DM * 128;                 // pieces per LDS stage
 
   f32x4 acc[DN][DM];
@@ -43,51 +73,77 @@ __global__ __launch_bounds__(256) void gemm_dense_kernel(const GemmArgs a) {
 #pragma unroll
     for (int j = 0; j < DM; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  u32x4 wa[DKS][DN], wn[DKS][DN], xs[DKS][DM / 2];
+  // Two register sets of A tiles (wa, wb) alternate between "being multiplied" and "being
+  // loaded"; B tiles go global -> registers (xs) -> the other LDS stage.  The loads of stage
+  // s+1 are issued before the MFMAs of stage s (sched_barrier keeps them there) and are
+  // parked in LDS half-way through them, so nothing but the barrier separates two stages.
+  u32x4 wa[DKS][DN], wb[DKS][DN], xs[DKS][DM / 2];
+  auto issue = [&](u32x4 (&wr)[DKS][DN]) {
+    // B first: the LDS write only has to wait for these (the counter retires loads in order)
 #pragma unroll
-  for (int ks = 0; ks < DKS; ++ks) {
+    for (int ks = 0; ks < DKS; ++ks)
 #pragma unroll
-    for (int i = 0; i < DN; ++i) wa[ks][i] = wp[ks * kstride + i * 64];
+      for (int i = 0; i < DM / 2; ++i) xs[ks][i] = __builtin_amdgcn_raw_buffer_load_b128(rx, xl, xq + ks * kts_b + i * 4096, 0);
 #pragma unroll
-    for (int i = 0; i < DM / 2; ++i) xs[ks][i] = xsrc[ks * kts + i * 256];
-  }
+    for (int ks = 0; ks < DKS; ++ks)
 #pragma unroll
-  for (int ks = 0; ks < DKS; ++ks)
+      for (int i = 0; i < DN; ++i) wr[ks][i] = __builtin_amdgcn_raw_buffer_load_b128(rw, wl + i * 1024, wq + ks * kstride_b, 0);
+  };
+  auto stash = [&](int buf) {
+    u32x4 *dst = bs + buf * STAGE + tid;
 #pragma unroll
-    for (int i = 0; i < DM / 2; ++i) bs[ks * (DM * 128) + i * 256 + tid] = xs[ks][i];
-  __syncthreads();
-
-  const int NS = a.KT / DKS;
-  for (int st = 0; st < NS; ++st) {
-    const int cur = st & 1;
-    const size_t tn = (size_t)min(st + 1, NS - 1) * DKS;   // the last stage re-issues its own loads (ignored)
+    for (int ks = 0; ks < DKS; ++ks)
 #pragma unroll
-    for (int ks = 0; ks < DKS; ++ks) {
+      for (int i = 0; i < DM / 2; ++i) dst[ks * (DM * 128) + i * 256] = xs[ks][i];
+  };
+  // MFMAs of one stage.  The B tiles of step t+1 are read from LDS while the 2*DN MFMAs of
+  // step t run, and the next stage's B tiles are written to the other LDS stage after half of
+  // the steps; the sched_group_barrier sequence pins that interleaving.
+  auto multiply = [&](const u32x4 (&wr)[DKS][DN], int buf) {
+    const u32x4 *bcur = bs + buf * STAGE + lane;
+    constexpr int T = DKS * DM, STASH_AT = T - 2;
+    u32x4 f[2][2];
+    f[0][0] = bcur[0];
+    f[0][1] = bcur[64];
 #pragma unroll
-      for (int i = 0; i < DN; ++i) wn[ks][i] = wp[(tn + ks) * kstride + i * 64];
-#pragma unroll
-      for (int i = 0; i < DM / 2; ++i) xs[ks][i] = xsrc[(tn + ks) * kts + i * 256];
-    }
-    const u32x4 *bcur = bs + cur * STAGE + m * 4 + g;   // packed slot of (row m, k-octet g)
-#pragma unroll
-    for (int ks = 0; ks < DKS; ++ks) {
-#pragma unroll
-      for (int j = 0; j < DM; ++j) {
-        const u32x4 bh = bcur[(ks * DM + j) * 128], bl = bcur[(ks * DM + j) * 128 + 64];
-#pragma unroll
-        for (int i = 0; i < DN; ++i) acc[i][j] = mfma_bf16(wa[ks][i], bh, acc[i][j]);
-#pragma unroll
-        for (int i = 0; i < DN; ++i) acc[i][j] = mfma_bf16(wa[ks][i], bl, acc[i][j]);
+    for (int t = 0; t < T; ++t) {
+      const int ks = t / DM, j = t % DM;
+      if (t + 1 < T) {
+        f[(t + 1) & 1][0] = bcur[(t + 1) * 128];
+        f[(t + 1) & 1][1] = bcur[(t + 1) * 128 + 64];
       }
+#pragma unroll
+      for (int i = 0; i < DN; ++i) acc[i][j] = mfma_bf16(wr[ks][i], f[t & 1][0], acc[i][j]);
+#pragma unroll
+      for (int i = 0; i < DN; ++i) acc[i][j] = mfma_bf16(wr[ks][i], f[t & 1][1], acc[i][j]);
+      if (t == STASH_AT) stash(buf ^ 1);
     }
-    u32x4 *bnext = bs + (cur ^ 1) * STAGE + tid;
+    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);        // DS reads of step 0
 #pragma unroll
-    for (int ks = 0; ks < DKS; ++ks) {
-#pragma unroll
-      for (int i = 0; i < DM / 2; ++i) bnext[ks * (DM * 128) + i * 256] = xs[ks][i];
-#pragma unroll
-      for (int i = 0; i < DN; ++i) wa[ks][i] = wn[ks][i];
+    for (int t = 0; t < T; ++t) {
+      if (t + 1 < T) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // DS reads of step t+1
+      __builtin_amdgcn_sched_group_barrier(0x008, 2 * DN, 0);            // MFMAs of step t
+      if (t == STASH_AT) __builtin_amdgcn_sched_group_barrier(0x200, DKS * DM / 2, 0);   // DS writes
     }
+  };
+  const int NS = a.KT / DKS;   // even: K is a multiple of 256
+  const unsigned wstep = DKS * kstride_b, xstep = DKS * kts_b;
+  issue(wa);
+  stash(0);
+  wq += wstep; xq += xstep;
+  __syncthreads();
+  for (int st = 0; st < NS; st += 2) {
+    issue(wb);                       // stage st+1
+    if (st + 2 < NS) { wq += wstep; xq += xstep; }   // the last stage re-issues its own loads (ignored)
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(wa, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+    issue(wa);                       // stage st+2
+    if (st + 2 < NS) { wq += wstep; xq += xstep; }
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(wb, 1);
+    __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
   }
 
@@ -95,7 +151,7 @@ __global__ __launch_bounds__(256) void gemm_dense_kernel(const GemmArgs a) {
 #pragma unroll
   for (int i = 0; i < DN; i += STEP) {
     const int nb = nbw + i;
-    if (nb < (int)blockIdx.x * (4 * DN)) continue;   // slid-back duplicate of a neighbour's row-block
+    if (nb < tn * (4 * DN)) continue;   // slid-back duplicate of a neighbour's row-block
 #pragma unroll
     for (int j = 0; j < DM; ++j) {
       const int rb = rb0 + j, row = rb * 16 + m;
@@ -106,16 +162,27 @@ __global__ __launch_bounds__(256) void gemm_dense_kernel(const GemmArgs a) {
   }
 }
 
-template <int EPI, bool NORM>
-static void launch_dense_cfg(const GemmArgs &a, hipStream_t s) {
+template <int EPI, bool NORM, int DM>
+static void launch_dense_tile(const GemmArgs &a, hipStream_t s) {
   constexpr int sm = 2 * DKS * DM * 128 * 16;
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute((const void *)gemm_dense_kernel<EPI, NORM>, hipFuncAttributeMaxDynamicSharedMemorySize, sm);
+    (void)hipFuncSetAttribute((const void *)gemm_dense_kernel<EPI, NORM, DM>, hipFuncAttributeMaxDynamicSharedMemorySize, sm);
     attr_set = true;
   }
-  const dim3 grid((a.NBtot + 4 * DN - 1) / (4 * DN), (a.rows + DM * 16 - 1) / (DM * 16));
-  gemm_dense_kernel<EPI, NORM><<<grid, 256, sm, s>>>(a);
+  const int tiles = ((a.NBtot + 4 * DN - 1) / (4 * DN)) * ((a.rows + DM * 16 - 1) / (DM * 16));
+  gemm_dense_kernel<EPI, NORM, DM><<<(tiles + 7) / 8 * 8, 256, sm, s>>>(a);
+}
+
+template <int EPI, bool NORM>
+static void launch_dense_cfg(const GemmArgs &a, hipStream_t s) {
+  // 256 compute units x 2 resident workgroups: estimate both tilings in rounds of 512
+  // workgroups; a 64-row tile costs about 0.55 of a 128-row one.
+  const long nt = (a.NBtot + 4 * DN - 1) / (4 * DN);
+  const long t8 = nt * ((a.rows + 127) / 128), t4 = nt * ((a.rows + 63) / 64);
+  const double c8 = (double)((t8 + 511) / 512), c4 = 0.55 * (double)((t4 + 511) / 512);
+  if (c4 < c8) launch_dense_tile<EPI, NORM, 4>(a, s);
+  else launch_dense_tile<EPI, NORM, 8>(a, s);
 }
 
 void launch_gemm_dense(const GemmLaunch &L, int RB, const float *rinv, hipStream_t s) {
@@ -126,6 +193,8 @@ void launch_gemm_dense(const GemmLaunch &L, int RB, const float *rinv, hipStream
   a.Xp = (const u32x4 *)L.Xp;
   a.rows = L.rows;
   a.RB = RB;
+  a.w_bytes = (int)((size_t)L.W->N * L.W->K * 2);
+  a.xp_bytes = (int)((size_t)L.W->K * RB * 64);
   a.rinv = rinv;
   a.bias = L.bias;
   a.Xp_out = (u32x4 *)L.Xp_out; a.gain_out = L.gain_out; a.ssq_out = L.ssq_out;
