@@ -5,11 +5,14 @@
 // live in the packed bf16 hi/lo form of the decode step, extended to many row-blocks
 // (Xp[kt][rb][h][64], see packed.h); weights are the same k-major MFMA tiles the decode
 // GEMMs stream.  Kernels:
-//  * gemm_dense_kernel: workgroup tile = 256 weight rows x 128 activation rows.  Each of the
-//    4 waves owns 4 weight row-blocks (A operands loaded straight from the tiled matrix, one
-//    coalesced 1 KB burst per tile) and all 8 activation row-blocks, which the workgroup
-//    stages through double-buffered LDS (32 KB per stage of 2 k-tiles).  64 MFMAs per wave
-//    and k-tile against 16 LDS reads; epilogues are those of the decode GEMM.
+//  * gemm_dense_kernel: workgroup tile = 256 weight rows x 128 (or 64) activation rows.  Each
+//    of the 4 waves owns 4 weight row-blocks (A operands: buffer loads straight from the tiled
+//    matrix into registers, one coalesced 1 KB burst per tile, double-buffered) and all 8 (4)
+//    activation row-blocks, which the workgroup stages through double-buffered LDS (32 KB per
+//    stage of 2 k-tiles).  64 MFMAs per wave and k-tile against 16 LDS reads, which are issued
+//    one step ahead of the MFMAs that use them; two workgroups per CU (<= 256 registers) so
+//    that two waves feed every matrix pipe; tiles are handed out XCD-aware; epilogues are
+//    those of the decode GEMM.
 //  * attn_prefill_kernel: causal flash attention straight off the tiled KV cache; a wave owns
 //    16 (row, head) pairs of one KV head and walks the visible keys 64 at a time with an
 //    online softmax in the log2 domain; no partials, no merge, packed output.
@@ -34,7 +37,8 @@ __global__ __launch_bounds__(256, 2) void gemm_dense_kernel(const GemmArgs a) {
   // has its own L2, so XCD x takes a contiguous share of the tile list, and the list runs
   // through panels of 8 weight tiles with the activation tile advancing every 8 entries: the
   // ~64 workgroups resident on an XCD then cover about 8 x 8 tiles and share their operands in
-  // that L2 (measured: 3.3 GB -> see the design notes of HBM traffic per 7B gate/up GEMM).
+  // that L2 (7B gate/up GEMM over 2048 rows: 1.4 GB fetched from HBM instead of 3.3 GB with
+  // the plain row-major order).
   const int NT = (a.NBtot + 4 * DN - 1) / (4 * DN), MT = (a.rows + DM * 16 - 1) / (DM * 16);
   const int per = (NT * MT + 7) >> 3;
   const int v = ((int)blockIdx.x & 7) * per + ((int)blockIdx.x >> 3);

@@ -148,3 +148,60 @@ def test_prefill_mode_argument_errors():
         eng.set_prefill_mode(Engine.PREFILL_DENSE)
     assert e.value.code == AE_EUNSUPPORTED
     eng.close()
+
+
+def test_7b_shape_dense_prefill_matches_oracle():
+    """Full 7B shape (32 layers): a 160-token prompt (one full 128-row tile plus a ragged one)
+    through the dense pass against the oracle's block-wise prompt pass."""
+    from paper_2412_18910_amd.config import LLAMA_7B
+    cfg = LLAMA_7B.with_(n_ctx_max=256)
+    eng, orc, _ = make_pair(cfg, 1)
+    n = 160
+    ids = synth.token_ids(n, cfg.vocab, 77)
+    orc.prefill(ids)
+    eng.set_prefill_mode(Engine.PREFILL_DENSE)
+    eng.prefill(ids)
+    lo, lg = orc.logits(0), eng.logits(0)
+    assert np.max(np.abs(lo - lg)) <= TOL, float(np.max(np.abs(lo - lg)))
+    if top2_margin(lo) > MARGIN:
+        assert eng.pending == orc.pending
+    for layer in (0, 31, 32):
+        for slot in (0, 127, 128, 158):
+            a, b = orc.kv_row(layer, 0, slot), eng.kv_row(layer, 0, slot)
+            assert np.max(np.abs(a - b)) <= np.max(np.abs(a)) * 2 ** -7 + 1e-6, (layer, slot)
+    # one decode step on top of the dense-prefilled caches (draft head included)
+    d_o = orc.draft(3)
+    d_g = eng.draft(3, override_ids=d_o)
+    assert np.array_equal(d_o, d_g)
+    orc.verify(n_rows=4)
+    eng.verify(n_rows=4)
+    for row in range(4):
+        assert np.max(np.abs(orc.logits(row) - eng.logits(row))) <= TOL, row
+    eng.close()
+
+
+def test_7b_shape_2048_token_prompt_dense_agrees_with_block_pass():
+    """The benchmark's prompt (2048 tokens, 7B shape, one 2048-row chunk) is too long for the
+    oracle; at that size the dense pass is checked against the 16-row pass of the decode
+    kernels, which the other tests tie to the oracle: last-position logits and feature, first
+    token, and sampled cache rows of the first / last target layer and of the draft head."""
+    from paper_2412_18910_amd.config import LLAMA_7B
+    cfg = LLAMA_7B.with_(n_ctx_max=2048 + 64)
+    w = synth.make_weights(cfg, 1, device="cuda:0")
+    eng = Engine(cfg, w)
+    ids = synth.token_ids(2048, cfg.vocab, 11)
+    res = {}
+    for mode in (Engine.PREFILL_BLOCKS, Engine.PREFILL_DENSE):
+        eng.set_prefill_mode(mode)
+        eng.prefill(ids)
+        res[mode] = dict(logits=eng.logits(0), feat=eng.feature(2047 % 16), pending=eng.pending,
+                         kv={(l, wh, s): eng.kv_row(l, wh, s) for l in (0, 31, 32) for wh in (0, 1)
+                             for s in (0, 1, 1023, 1024, 2046)})
+    b, d = res[Engine.PREFILL_BLOCKS], res[Engine.PREFILL_DENSE]
+    assert np.max(np.abs(b["logits"] - d["logits"])) <= TOL
+    assert np.max(np.abs(b["feat"] - d["feat"])) <= 0.1
+    if top2_margin(b["logits"]) > MARGIN:
+        assert b["pending"] == d["pending"]
+    for key, a in b["kv"].items():
+        assert np.max(np.abs(a - d["kv"][key])) <= np.max(np.abs(a)) * 2 ** -6 + 1e-6, key
+    eng.close()
