@@ -170,29 +170,54 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const float *q, int rows
   }
 }
 
-// Merge of the chunk partials (log2-domain maxima) in fixed chunk order; grid rows*H,
-// block HD/4 (four head-dim elements per thread).  The result is written in packed form
-// as the input of the output projection (k index = h*HD + d).
+// Merge of the chunk partials (log2-domain maxima); one workgroup of 256 threads per (row,
+// head): HD/4 threads across the head dimension (four elements each) times 1024/HD chunk
+// lanes, so the partials of many chunks are in flight at once.  Chunk lane cl sums chunks cl,
+// cl+CL, ... in ascending order and the lanes are combined in ascending order: a fixed order
+// that does not depend on the number of rows.  The result is written in packed form as the
+// input of the output projection (k index = h*HD + d).
 template <int HD>
-__global__ void attn_merge_log2_kernel(const float *part, int rows, int H, int Hkv, int n_chunks, u32x4 *Xp_out) {
-  const int mrow = blockIdx.x / H, h = blockIdx.x % H, d = threadIdx.x * 4;
+__global__ __launch_bounds__(256) void attn_merge_log2_kernel(const float *part, int rows, int H, int Hkv, int n_chunks,
+                                                              u32x4 *Xp_out) {
+  constexpr int DQ = HD / 4, CL = 256 / DQ;
+  __shared__ float ms[kMaxSplits];
+  __shared__ float4 nums[CL][DQ];
+  __shared__ float dens[CL];
+  const int mrow = blockIdx.x / H, h = blockIdx.x % H, dq = threadIdx.x % DQ, cl = threadIdx.x / DQ;
   const int G = H / Hkv, kh = h / G, r = mrow * G + (h % G), R = rows * G;
+  const float *base = part + ((size_t)kh * n_chunks * R + r) * (HD + 2);
+  const size_t cstride = (size_t)R * (HD + 2);
+  for (int c = threadIdx.x; c < n_chunks; c += 256) ms[c] = base[c * cstride + HD];
+  __syncthreads();
   float mx = -INFINITY;
-  for (int c = 0; c < n_chunks; ++c) mx = fmaxf(mx, part[(((size_t)kh * n_chunks + c) * R + r) * (HD + 2) + HD]);
+  for (int c = 0; c < n_chunks; ++c) mx = fmaxf(mx, ms[c]);
   float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
   float den = 0.f;
-  for (int c = 0; c < n_chunks; ++c) {
-    const float *p = part + (((size_t)kh * n_chunks + c) * R + r) * (HD + 2);
-    const float mc = p[HD];
+#pragma unroll 2
+  for (int c = cl; c < n_chunks; c += CL) {
+    const float mc = ms[c];
+    const float *p = base + c * cstride;
+    const float2 a = *reinterpret_cast<const float2 *>(p + dq * 4), b = *reinterpret_cast<const float2 *>(p + dq * 4 + 2);
+    const float lc = p[HD + 1];
     if (mc > -INFINITY) {
       const float wgt = __builtin_amdgcn_exp2f(mc - mx);
-      const float2 a = *reinterpret_cast<const float2 *>(p + d), b = *reinterpret_cast<const float2 *>(p + d + 2);
       num.x = fmaf(wgt, a.x, num.x); num.y = fmaf(wgt, a.y, num.y);
       num.z = fmaf(wgt, b.x, num.z); num.w = fmaf(wgt, b.y, num.w);
-      den = fmaf(wgt, p[HD + 1], den);
+      den = fmaf(wgt, lc, den);
     }
   }
-  packed_store4(Xp_out, mrow, h * HD + d, num.x / den, num.y / den, num.z / den, num.w / den);
+  nums[cl][dq] = num;
+  if (dq == 0) dens[cl] = den;
+  __syncthreads();
+  if (cl == 0) {
+#pragma unroll
+    for (int i = 1; i < CL; ++i) {
+      const float4 o = nums[i][dq];
+      num.x += o.x; num.y += o.y; num.z += o.z; num.w += o.w;
+      den += dens[i];
+    }
+    packed_store4(Xp_out, mrow, h * HD + dq * 4, num.x / den, num.y / den, num.z / den, num.w / den);
+  }
 }
 
 void launch_attention_mfma(const float *q, int rows, int pos0, const ae_config &c, const void *kv_layer, size_t v_off,
@@ -209,12 +234,12 @@ void launch_attention_mfma(const float *q, int rows, int pos0, const ae_config &
     if (sm > 48 * 1024)
       (void)hipFuncSetAttribute((const void *)attn_mfma_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
     attn_mfma_kernel<128><<<grid, 256, sm, s>>>(q, rows, pos0, c.n_heads, c.n_kv_heads, cap, Kc, Vc, part, scale_log2e);
-    attn_merge_log2_kernel<128><<<rows * c.n_heads, 32, 0, s>>>(part, rows, c.n_heads, c.n_kv_heads, n_chunks, (u32x4 *)Xp_out);
+    attn_merge_log2_kernel<128><<<rows * c.n_heads, 256, 0, s>>>(part, rows, c.n_heads, c.n_kv_heads, n_chunks, (u32x4 *)Xp_out);
   } else {
     if (sm > 48 * 1024)
       (void)hipFuncSetAttribute((const void *)attn_mfma_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
     attn_mfma_kernel<64><<<grid, 256, sm, s>>>(q, rows, pos0, c.n_heads, c.n_kv_heads, cap, Kc, Vc, part, scale_log2e);
-    attn_merge_log2_kernel<64><<<rows * c.n_heads, 16, 0, s>>>(part, rows, c.n_heads, c.n_kv_heads, n_chunks, (u32x4 *)Xp_out);
+    attn_merge_log2_kernel<64><<<rows * c.n_heads, 256, 0, s>>>(part, rows, c.n_heads, c.n_kv_heads, n_chunks, (u32x4 *)Xp_out);
   }
 }
 
