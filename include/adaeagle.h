@@ -63,6 +63,9 @@ typedef struct {
   float temperature;     /* 0: greedy (Sec. 3.1); > 0: rejection sampling (Sec. 2.1) */
   int32_t ddd_enabled;   /* AdaEAGLE-DDD exit rule (Sec. 3.4, 4.2); greedy only */
   float ddd_threshold;   /* log-probability threshold of that rule (the paper picks -0.6) */
+  int32_t ldlp_cls;      /* 0: LDLP regresses a scalar, rounded and clamped (Eq. 3)
+                            1: classification over the lengths 0..k_max (the "w/ Cls"
+                               ablation of Sec. 4.3): k = argmax of k_max+1 scores */
 } ae_config;
 
 /* One pre-norm Llama-style decoder layer (device pointers). */
@@ -86,8 +89,8 @@ typedef struct {
   const float *ldlp_b_in;     /* [h] */
   const void *ldlp_w_res;     /* [n_res, h, h] or NULL */
   const float *ldlp_b_res;    /* [n_res, h] or NULL */
-  const float *ldlp_w_out;    /* [h] */
-  const float *ldlp_b_out;    /* [1] */
+  const float *ldlp_w_out;    /* [h]; with ldlp_cls: [k_max+1, h] */
+  const float *ldlp_b_out;    /* [1]; with ldlp_cls: [k_max+1] */
 } ae_weights;
 
 /* Validates cfg, re-tiles bf16 matrices, allocates the KV cache and work buffers on the
@@ -124,7 +127,9 @@ int ae_set_state(ae_ctx *ctx, int kv_len, int32_t last_tok, int32_t pending, con
 
 /* Eq. 3: k = min(k_max, max(0, Round(MLP(e, f)))), round half to even.  e is the
  * embedding of the last validated token, f its post-final-norm hidden state.
- * y_out (nullable) receives the scalar before rounding. */
+ * y_out (nullable) receives the scalar before rounding.  With cfg.ldlp_cls the MLP's last
+ * layer scores the lengths 0..k_max, k is the best-scoring length (the lowest on ties)
+ * and y_out its score. */
 int ae_ldlp(ae_ctx *ctx, int *k_out, float *y_out);
 
 /* Eq. 2: draft catch-up over the newly validated slots, then a chain of k-1 further

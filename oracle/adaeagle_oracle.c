@@ -457,11 +457,25 @@ int orc_ldlp(orc_model *m, int *k_out, float *y_out) {
     matmul(Wr, c->wdtype, h, h, z, 1, h, m->w.ldlp_b_res + (size_t)r * h, t, h);
     for (int i = 0; i < h; ++i) z[i] += silu(t[i]);
   }
-  acc_t a = 0;
-  for (int i = 0; i < h; ++i) a += (acc_t)silu(z[i]) * (acc_t)m->w.ldlp_w_out[i];
-  const float y = (float)a + m->w.ldlp_b_out[0];
-  if (y_out) *y_out = y;
-  *k_out = orc_round_clamp(y, c->k_max);
+  if (c->ldlp_cls) {
+    /* one score per candidate length 0..k_max; the best score names the length */
+    int best = 0;
+    float best_y = 0.0f;
+    for (int cl = 0; cl <= c->k_max; ++cl) {
+      acc_t a = 0;
+      for (int i = 0; i < h; ++i) a += (acc_t)silu(z[i]) * (acc_t)m->w.ldlp_w_out[(size_t)cl * h + i];
+      const float y = (float)a + m->w.ldlp_b_out[cl];
+      if (cl == 0 || y > best_y) { best = cl; best_y = y; }
+    }
+    if (y_out) *y_out = best_y;
+    *k_out = best;
+  } else {
+    acc_t a = 0;
+    for (int i = 0; i < h; ++i) a += (acc_t)silu(z[i]) * (acc_t)m->w.ldlp_w_out[i];
+    const float y = (float)a + m->w.ldlp_b_out[0];
+    if (y_out) *y_out = y;
+    *k_out = orc_round_clamp(y, c->k_max);
+  }
   free(u); free(z); free(t);
   return 0;
 }
@@ -607,4 +621,14 @@ const float *orc_feature(const orc_model *m, int row) { return m->F + (size_t)ro
 const float *orc_draft_logits(const orc_model *m, int i) { return m->dlogits + (size_t)i * m->c.vocab; }
 const float *orc_kv_row(const orc_model *m, int layer, int which, int slot) {
   return (which ? m->V[layer] : m->K[layer]) + (size_t)slot * m->d_kv;
+}
+
+/* Sec. 3.3, optimisation criterion: L1 distance, times lambda when the prediction is short. */
+double orc_ldlp_loss(const float *pred, const int32_t *truth, int n, double lambda) {
+  double tot = 0.0;
+  for (int i = 0; i < n; ++i) {
+    const double diff = (double)pred[i] - (double)truth[i];
+    tot += diff < 0.0 ? lambda * -diff : diff;
+  }
+  return n > 0 ? tot / n : 0.0;
 }

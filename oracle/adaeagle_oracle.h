@@ -47,6 +47,8 @@ typedef struct {
   float temperature;     /* 0 => greedy */
   int32_t ddd_enabled;   /* AdaEAGLE-DDD (Sec. 3.4): keep drafting past the predicted length ... */
   float ddd_threshold;   /* ... while the draft sequence's log-probability is >= this value */
+  int32_t ldlp_cls;      /* 0: Eq. 3 (scalar, round, clamp)   1: argmax over k_max+1 class scores
+                            (classification variant of the Sec. 4.3 ablation) */
 } orc_config;
 
 /* One decoder layer: matrices row-major [out, in] in cfg.wdtype, norm gains float[d]. */
@@ -69,8 +71,8 @@ typedef struct {
   const float *ldlp_b_in;    /* [h] */
   const void *ldlp_w_res;    /* [n_res, h, h] or NULL */
   const float *ldlp_b_res;   /* [n_res, h] or NULL */
-  const float *ldlp_w_out;   /* [h] */
-  const float *ldlp_b_out;   /* [1] */
+  const float *ldlp_w_out;   /* [h]; ldlp_cls: [k_max+1, h] */
+  const float *ldlp_b_out;   /* [1]; ldlp_cls: [k_max+1] */
 } orc_weights;
 
 typedef struct orc_model orc_model;
@@ -90,7 +92,8 @@ int orc_kv_import(orc_model *m, int layer, const float *k, const float *v, int n
  * one valid feature row (position n) and the token at position n. */
 int orc_set_state(orc_model *m, int kv_len, int32_t last_tok, int32_t pending, const float *feat);
 
-/* Eq. 3.  y_out (nullable) receives the raw scalar before rounding. */
+/* Eq. 3.  y_out (nullable) receives the raw scalar before rounding (ldlp_cls: the winning
+ * class score; the lowest length wins ties). */
 int orc_ldlp(orc_model *m, int *k_out, float *y_out);
 /* Eq. 2: catch-up over newly validated slots, then chain to k tokens.  With ddd_enabled
  * (Sec. 3.4, 4.2) the head exits before token s iff s > k AND the log-probability of the
@@ -138,6 +141,9 @@ int orc_accept_sample(const float *target_logits, const float *draft_logits, int
 int orc_accept_greedy(const float *target_logits, int vocab, int k, const int32_t *draft_ids,
                       int *n_accepted, int32_t *bonus);
 int32_t orc_sample_inverse_cdf(const double *q, int n, double u);
+/* LDLP training criterion (Sec. 3.3): mean over n pairs of |pred - truth|, scaled by lambda
+ * where pred < truth (predicting too short costs a target forward, too long only draft steps). */
+double orc_ldlp_loss(const float *pred, const int32_t *truth, int n, double lambda);
 
 #ifdef __cplusplus
 }

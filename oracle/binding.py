@@ -20,7 +20,7 @@ class OrcConfig(C.Structure):
         ("rope_base", C.c_float), ("rms_eps", C.c_float), ("wdtype", C.c_int32),
         ("k_max", C.c_int32), ("n_ctx_max", C.c_int32), ("ldlp_in_mode", C.c_int32),
         ("ldlp_hidden", C.c_int32), ("ldlp_n_res", C.c_int32), ("temperature", C.c_float),
-        ("ddd_enabled", C.c_int32), ("ddd_threshold", C.c_float)]
+        ("ddd_enabled", C.c_int32), ("ddd_threshold", C.c_float), ("ldlp_cls", C.c_int32)]
 
 
 class OrcLayer(C.Structure):
@@ -85,6 +85,7 @@ def load(acc_double=False):
         "orc_accept_sample": (I, [f32p, f32p, I, I, i32p, D, f64p, C.POINTER(I), i32p]),
         "orc_accept_greedy": (I, [f32p, I, I, i32p, C.POINTER(I), i32p]),
         "orc_sample_inverse_cdf": (C.c_int32, [f64p, I, D]),
+        "orc_ldlp_loss": (D, [f32p, i32p, I, D]),
     }
     for name_, (res, args) in sig.items():
         fn = getattr(lib, name_)

@@ -30,7 +30,7 @@ class AeConfig(C.Structure):
         ("rope_base", C.c_float), ("rms_eps", C.c_float), ("dtype", C.c_int32), ("k_max", C.c_int32),
         ("n_ctx_max", C.c_int32), ("ldlp_in_mode", C.c_int32), ("ldlp_hidden", C.c_int32),
         ("ldlp_n_res", C.c_int32), ("temperature", C.c_float), ("ddd_enabled", C.c_int32),
-        ("ddd_threshold", C.c_float)]
+        ("ddd_threshold", C.c_float), ("ldlp_cls", C.c_int32)]
 
 
 class AeLayerW(C.Structure):

@@ -24,6 +24,7 @@ class Config:
     temperature: float = 0.0     # 0 => greedy
     ddd_enabled: int = 0         # AdaEAGLE-DDD exit rule (Sec. 3.4)
     ddd_threshold: float = -0.6  # log-probability threshold (Sec. 4.3.3)
+    ldlp_cls: int = 0            # 1: LDLP classifies over 0..k_max instead of regressing (Sec. 4.3 ablation)
 
     def dict(self):
         return asdict(self)

@@ -218,7 +218,7 @@ void enqueue_ldlp(ae_ctx *c, int slot, int f_row, bool relative_to_accept) {
   launch_gemm_generic(c->ldlp_in.rowmajor, g.dtype, g.ldlp_hidden, in, c->ldlp_u, in, 1, c->ldlp_b_in, c->ldlp_z,
                       g.ldlp_hidden, 0, s);
   launch_ldlp_tail(c->ldlp_z, c->ldlp_w_res, g.dtype, c->ldlp_b_res, c->ldlp_w_out, c->ldlp_b_out, g.ldlp_hidden,
-                   g.ldlp_n_res, g.k_max, c->st, s);
+                   g.ldlp_n_res, g.k_max, g.ldlp_cls, c->st, s);
 }
 
 // after a stream synchronisation: fold the finished event pairs into the totals
@@ -387,7 +387,8 @@ int ae_init(const ae_config *cfg, const ae_weights *w, void *hip_stream, ae_ctx 
       g.n_heads % g.n_kv_heads != 0 || g.k_max < 0 || g.n_ctx_max < 1 || g.ldlp_hidden < 1 || g.ldlp_n_res < 0 ||
       (g.dtype != AE_BF16 && g.dtype != AE_FP32) || (g.ldlp_in_mode != 0 && g.ldlp_in_mode != 1) ||
       !(g.temperature >= 0.f) || !(g.rms_eps >= 0.f) || !(g.rope_base > 0.f) ||
-      (g.ddd_enabled != 0 && g.ddd_enabled != 1) || (g.ddd_enabled && !(g.ddd_threshold == g.ddd_threshold)))
+      (g.ddd_enabled != 0 && g.ddd_enabled != 1) || (g.ddd_enabled && !(g.ddd_threshold == g.ddd_threshold)) ||
+      (g.ldlp_cls != 0 && g.ldlp_cls != 1))
     return fail(nullptr, AE_EINVAL, "ae_init: configuration field out of range");
   if (g.head_dim != 64 && g.head_dim != 128) return fail(nullptr, AE_EUNSUPPORTED, "head_dim must be 64 or 128");
   if (g.k_max + 1 > kMaxRows) return fail(nullptr, AE_EUNSUPPORTED, "k_max must be <= 15");

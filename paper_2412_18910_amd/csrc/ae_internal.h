@@ -145,7 +145,7 @@ void launch_accept_greedy(DevState *st, int32_t *hist, int kv_len, int rows, hip
 void launch_ldlp_gather(const void *emb, int dtype, const int32_t *hist, const float *F, int d, int in_mode,
                         int kv_len_minus1_or_neg, int f_row, const DevState *st, float *u, hipStream_t s);
 void launch_ldlp_tail(const float *z0, const void *w_res, int dtype, const float *b_res, const float *w_out,
-                      const float *b_out, int h, int n_res, int k_max, DevState *st, hipStream_t s);
+                      const float *b_out, int h, int n_res, int k_max, int cls, DevState *st, hipStream_t s);
 void launch_rope_table(float2 *tab, int n_pos, int head_dim, float base, hipStream_t s);
 void launch_fill_zero(void *p, size_t bytes, hipStream_t s);
 

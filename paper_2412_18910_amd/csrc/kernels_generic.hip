@@ -289,11 +289,13 @@ void launch_ldlp_gather(const void *emb, int dtype, const int32_t *hist, const f
 }
 
 // z0 = W_in u + b_in comes from the GEMM; here: residual blocks z += silu(W_r z + b_r),
-// y = w_out . silu(z) + b_out, k = clamp(round_half_even(y), 0, k_max).
+// y = w_out . silu(z) + b_out, k = clamp(round_half_even(y), 0, k_max)  (Eq. 3).
+// cls != 0: the classification variant (Sec. 4.3 ablation), one score per length 0..k_max,
+// k = argmax (lowest length on ties), y_next = the winning score.
 template <typename T>
 __global__ __launch_bounds__(1024) void ldlp_tail_kernel(const float *z0, const T *w_res, const float *b_res,
                                                          const float *w_out, const float *b_out, int h, int n_res,
-                                                         int k_max, DevState *st) {
+                                                         int k_max, int cls, DevState *st) {
   __shared__ float z[kMaxLdlpHidden];
   __shared__ float t[kMaxLdlpHidden];
   const int i = threadIdx.x;
@@ -310,28 +312,39 @@ __global__ __launch_bounds__(1024) void ldlp_tail_kernel(const float *z0, const 
     if (i < h) z[i] += t[i];
     __syncthreads();
   }
-  t[i] = i < h ? silu_f(z[i]) * w_out[i] : 0.f;
-  __syncthreads();
-  for (int o = 512; o > 0; o >>= 1) {  // fixed-shape tree: deterministic
-    if (i < o) t[i] += t[i + o];
+  const float a = i < h ? silu_f(z[i]) : 0.f;
+  int best = 0;
+  float best_y = 0.f;
+  for (int c = 0; c < (cls ? k_max + 1 : 1); ++c) {
+    t[i] = i < h ? a * w_out[(size_t)c * h + i] : 0.f;
+    __syncthreads();
+    for (int o = 512; o > 0; o >>= 1) {  // fixed-shape tree: deterministic
+      if (i < o) t[i] += t[i + o];
+      __syncthreads();
+    }
+    const float y = t[0] + b_out[c];
+    if (c == 0 || y > best_y) { best = c; best_y = y; }
     __syncthreads();
   }
   if (i == 0) {
-    const float y = t[0] + b_out[0];
-    float r = rintf(y);  // round half to even
-    if (!(r >= 0.f)) r = 0.f;
-    if (r > (float)k_max) r = (float)k_max;
-    st->y_next = y;
-    st->k_next = (int)r;
+    st->y_next = best_y;
+    if (cls) {
+      st->k_next = best;
+    } else {
+      float r = rintf(best_y);  // round half to even
+      if (!(r >= 0.f)) r = 0.f;
+      if (r > (float)k_max) r = (float)k_max;
+      st->k_next = (int)r;
+    }
   }
 }
 
 void launch_ldlp_tail(const float *z0, const void *w_res, int dtype, const float *b_res, const float *w_out,
-                      const float *b_out, int h, int n_res, int k_max, DevState *st, hipStream_t s) {
+                      const float *b_out, int h, int n_res, int k_max, int cls, DevState *st, hipStream_t s) {
   if (dtype == AE_BF16)
-    ldlp_tail_kernel<bf16_t><<<1, 1024, 0, s>>>(z0, (const bf16_t *)w_res, b_res, w_out, b_out, h, n_res, k_max, st);
+    ldlp_tail_kernel<bf16_t><<<1, 1024, 0, s>>>(z0, (const bf16_t *)w_res, b_res, w_out, b_out, h, n_res, k_max, cls, st);
   else
-    ldlp_tail_kernel<float><<<1, 1024, 0, s>>>(z0, (const float *)w_res, b_res, w_out, b_out, h, n_res, k_max, st);
+    ldlp_tail_kernel<float><<<1, 1024, 0, s>>>(z0, (const float *)w_res, b_res, w_out, b_out, h, n_res, k_max, cls, st);
 }
 
 // ------------------------------------------------------------------ set-up helpers

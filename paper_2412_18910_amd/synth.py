@@ -61,8 +61,13 @@ def make_weights(cfg: Config, seed: int, device="cpu"):
         w["ldlp_b_res"] = None
     # spread the predicted length over 0..k_max instead of collapsing on one value
     s_out = (cfg.k_max / 4.0) / (math.sqrt(h) * 0.02 * math.sqrt(d) * 0.6)
-    w["ldlp_w_out"] = s_out * torch.randn(h, generator=g, device=device, dtype=torch.float32)
-    w["ldlp_b_out"] = torch.full((1,), (cfg.k_max + 1) / 2.0, device=device, dtype=torch.float32)
+    if cfg.ldlp_cls:
+        # one score row per candidate length; comparable spread so that every class wins sometimes
+        w["ldlp_w_out"] = s_out * torch.randn(cfg.k_max + 1, h, generator=g, device=device, dtype=torch.float32)
+        w["ldlp_b_out"] = 0.1 * torch.randn(cfg.k_max + 1, generator=g, device=device, dtype=torch.float32)
+    else:
+        w["ldlp_w_out"] = s_out * torch.randn(h, generator=g, device=device, dtype=torch.float32)
+        w["ldlp_b_out"] = torch.full((1,), (cfg.k_max + 1) / 2.0, device=device, dtype=torch.float32)
     return w
 
 

@@ -38,7 +38,7 @@ def test_struct_layouts_match_header():
     cfg = re.sub(r"/\*.*?\*/", "", cfg, flags=re.S)
     names = [n.strip() for decl in cfg.split(";") for n in re.sub(r"^\s*\w+\s", "", decl.strip()).split(",") if n.strip()]
     assert names == [n for n, _ in binding.AeConfig._fields_]
-    assert C.sizeof(binding.AeConfig) == 18 * 4
+    assert C.sizeof(binding.AeConfig) == 19 * 4
     assert C.sizeof(binding.AeLayerW) == 9 * 8
 
 

@@ -503,3 +503,46 @@ def test_two_contexts_are_independent():
         assert ta[1] == to[1] and np.array_equal(ta[2], to[2])
     eng_a.close()
     eng_b.close()
+
+
+@pytest.mark.parametrize("cfg0,seed", [(TINY, 0), (SMALL_BF16, 6)])
+def test_ldlp_classification_head_matches_oracle(cfg0, seed):
+    """Classification variant of the LDLP (Sec. 4.3 ablation): k_max+1 class scores, k = the
+    best-scoring length.  The winning score is compared always; the class wherever the top two
+    scores (float64 re-expression of the MLP on the oracle's own feature row) are clearly apart."""
+    import torch
+    F = torch.nn.functional
+    cfg = cfg0.with_(ldlp_cls=1, ldlp_n_res=1)
+    eng, orc, w = make_pair(cfg, seed)
+    n = 24
+    ids = synth.token_ids(n, cfg.vocab, seed + 50)
+    orc.prefill(ids)
+    eng.prefill(ids)
+    ytol = 1e-3 if cfg.dtype == FP32 else 0.1    # class scores have a spread of ~k_max/4
+    last_tok, f_row = int(ids[-1]), (n - 1) % (cfg.k_max + 1)
+    compared = 0
+    for r in range(10):
+        ko, yo = orc.ldlp()
+        kg, yg = eng.ldlp()
+        assert abs(yo - yg) < ytol, (r, yo, yg)
+        u = torch.cat([w["tok_emb"].double()[last_tok], torch.from_numpy(orc.feature(f_row)).double()])
+        z = F.linear(u, w["ldlp_w_in"].double(), w["ldlp_b_in"].double())
+        z = z + F.silu(F.linear(z, w["ldlp_w_res"][0].double(), w["ldlp_b_res"][0].double()))
+        scores = F.linear(F.silu(z), w["ldlp_w_out"].double(), w["ldlp_b_out"].double()).numpy()
+        assert ko == int(np.argmax(scores))
+        if top2_margin(scores) > 3 * ytol:
+            assert kg == ko, (r, scores)
+            compared += 1
+        k = min(ko, 3)
+        pend = orc.pending
+        d_o = orc.draft(k)
+        d_g = eng.draft(k, override_ids=d_o if k else None)
+        assert np.array_equal(d_o, d_g)
+        orc.verify(n_rows=k + 1)
+        eng.verify(n_rows=k + 1)
+        ao, ag = orc.accept(), eng.accept()
+        if ao != ag:
+            break
+        last_tok, f_row = (pend if ao[0] == 0 else int(d_o[ao[0] - 1])), ao[0]
+    assert compared >= 3
+    eng.close()

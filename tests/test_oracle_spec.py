@@ -237,3 +237,79 @@ def test_ddd_run_stays_lossless(ar_reference):
         ks.append(k)
     assert np.array_equal(np.array(out[:64]), ar[:64])
     assert max(ks) >= 1
+
+
+# ---- LDLP variants of the Sec. 4.3 ablation: classification head; the Sec. 3.3 criterion ----
+
+def test_ldlp_classification_matches_library_expression_and_picks_the_best_class():
+    cfg = TINY.with_(ldlp_cls=1, ldlp_n_res=1)
+    m, w = make_oracle(cfg, 12)
+    ids = synth.token_ids(10, cfg.vocab, 6)
+    m.prefill(ids)
+    k, y = m.ldlp()
+    f = torch.from_numpy(m.feature((10 - 1) % (cfg.k_max + 1))).double()
+    e = w["tok_emb"].double()[int(ids[-1])]
+    z = torch.nn.functional.linear(torch.cat([e, f]), w["ldlp_w_in"].double(), w["ldlp_b_in"].double())
+    z = z + torch.nn.functional.silu(torch.nn.functional.linear(z, w["ldlp_w_res"][0].double(), w["ldlp_b_res"][0].double()))
+    scores = torch.nn.functional.linear(torch.nn.functional.silu(z), w["ldlp_w_out"].double(), w["ldlp_b_out"].double())
+    assert scores.shape == (cfg.k_max + 1,)
+    assert k == int(torch.argmax(scores)) and abs(y - float(scores.max())) < 1e-4
+
+
+def test_ldlp_classification_closed_form_and_ties():
+    """Zero input layer: silu(z) is a constant vector, so class c scores s * sum(w_out[c]) + b_out[c];
+    with equal rows the bias alone decides and the lowest length wins a tie."""
+    cfg = TINY.with_(ldlp_cls=1)
+    w = dict(synth.make_weights(cfg, 0))
+    w["ldlp_w_in"] = torch.zeros_like(w["ldlp_w_in"])
+    w["ldlp_b_in"] = torch.full_like(w["ldlp_b_in"], 0.5)
+    w["ldlp_w_out"] = torch.ones_like(w["ldlp_w_out"])
+    ids = synth.token_ids(8, cfg.vocab, 5)
+    s = 0.5 / (1 + np.exp(-0.5)) * cfg.ldlp_hidden
+    for bias, want_k in (([0, 0, 0, 0, 0, 3, 0, 0, 0], 5), ([1, 0, 0, 2, 0, 2, 0, 0, 1], 3), ([0] * 9, 0)):
+        w["ldlp_b_out"] = torch.tensor(bias, dtype=torch.float32)
+        m, _ = make_oracle(cfg, 0, weights=w)
+        m.prefill(ids)
+        k, y = m.ldlp()
+        assert k == want_k and abs(y - (s + max(bias))) < 1e-3
+
+
+def test_ldlp_classification_drives_the_loop_losslessly(ar_reference):
+    """Same target and draft weights as the regression runs (the LDLP output layer is drawn
+    last), lengths now chosen by the classifier: the output is still the greedy sequence."""
+    ids, _, first, ar = ar_reference
+    cfg = TINY.with_(ldlp_cls=1)
+    m, _ = make_oracle(cfg, 0)
+    m.prefill(ids)
+    assert m.pending == first
+    out, ks = [], []
+    while len(out) < 64:
+        k, na, toks = m.step()
+        ks.append(k)
+        out.extend(int(t) for t in toks)
+    assert out[:64] == [int(t) for t in ar[:64]]
+    assert len(set(ks)) >= 2 and 0 <= min(ks) and max(ks) <= cfg.k_max
+
+
+def test_ldlp_loss_criterion():
+    """Sec. 3.3: |pred - truth|, times lambda when the prediction is too short."""
+    from oracle import binding as ob
+    from paper_2412_18910_amd.loop import ldlp_loss
+    from .helpers import f32, fp, ip
+    lib = ob.load()
+    pred = f32([3.0, 1.0, 5.0, 2.5, 0.0])
+    truth = np.array([3, 4, 2, 3, 0], np.int32)
+    # per pair: 0, 3*lam (short by 3), 3 (long by 3), 0.5*lam, 0
+    for lam in (1.0, 2.0, 3.5):
+        want = (0 + 3 * lam + 3 + 0.5 * lam + 0) / 5
+        assert abs(lib.orc_ldlp_loss(fp(pred), ip(truth), 5, lam) - want) < 1e-12
+        assert abs(ldlp_loss(pred, truth, lam) - want) < 1e-12
+    assert lib.orc_ldlp_loss(fp(pred), ip(truth), 0, 2.0) == 0.0
+    # lambda = 1 is plain L1; the penalty only ever raises the loss, and only on short predictions
+    rng = np.random.default_rng(0)
+    p, t = f32(rng.uniform(0, 8, 1000)), rng.integers(0, 9, 1000).astype(np.int32)
+    l1 = float(np.mean(np.abs(p.astype(np.float64) - t)))
+    assert abs(lib.orc_ldlp_loss(fp(p), ip(t), 1000, 1.0) - l1) < 1e-12
+    short = float(np.mean(np.clip(t - p.astype(np.float64), 0, None)))
+    assert abs(lib.orc_ldlp_loss(fp(p), ip(t), 1000, 3.0) - (l1 + 2.0 * short)) < 1e-12
+    assert abs(ldlp_loss(p, t, 3.0) - (l1 + 2.0 * short)) < 1e-12
