@@ -205,3 +205,28 @@ def test_7b_shape_2048_token_prompt_dense_agrees_with_block_pass():
     for key, a in b["kv"].items():
         assert np.max(np.abs(a - d["kv"][key])) <= np.max(np.abs(a)) * 2 ** -6 + 1e-6, key
     eng.close()
+
+
+def test_8b_gqa_shape_long_prompt_dense_agrees_with_block_pass():
+    """8B-GQA shape at reduced depth, 8192-token prompt in four 2048-row chunks (group size 4,
+    vocabulary 128256, rope base 5e5): dense pass against the 16-row pass of the decode kernels."""
+    from paper_2412_18910_amd.config import LLAMA_8B_GQA
+    n = 8192
+    cfg = LLAMA_8B_GQA.with_(n_layers=2, n_ctx_max=n + 64, temperature=0.0)
+    w = synth.make_weights(cfg, 2, device="cuda:0")
+    eng = Engine(cfg, w)
+    ids = synth.token_ids(n, cfg.vocab, 13)
+    res = {}
+    for mode in (Engine.PREFILL_BLOCKS, Engine.PREFILL_DENSE):
+        eng.set_prefill_mode(mode)
+        eng.prefill(ids)
+        res[mode] = dict(logits=eng.logits(0), pending=eng.pending,
+                         kv={(l, wh, s): eng.kv_row(l, wh, s) for l in (0, 1, 2) for wh in (0, 1)
+                             for s in (0, 2047, 2048, 6143, 8190)})
+    b, d = res[Engine.PREFILL_BLOCKS], res[Engine.PREFILL_DENSE]
+    assert np.max(np.abs(b["logits"] - d["logits"])) <= TOL
+    if top2_margin(b["logits"]) > MARGIN:
+        assert b["pending"] == d["pending"]
+    for key, a in b["kv"].items():
+        assert np.max(np.abs(a - d["kv"][key])) <= np.max(np.abs(a)) * 2 ** -6 + 1e-6, key
+    eng.close()
