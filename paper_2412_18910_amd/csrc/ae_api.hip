@@ -396,6 +396,8 @@ int ae_init(const ae_config *cfg, const ae_weights *w, void *hip_stream, ae_ctx 
     return fail(nullptr, AE_EUNSUPPORTED, "d_model, d_ffn, ldlp_hidden must be multiples of 8 (ldlp_hidden <= 1024)");
   if ((g.n_heads / g.n_kv_heads) * kMaxRows > 64)
     return fail(nullptr, AE_EUNSUPPORTED, "n_heads / n_kv_heads must be <= 4");
+  if (g.temperature > 0.f && g.vocab > 1024 * 1024)
+    return fail(nullptr, AE_EUNSUPPORTED, "temperature > 0 supports vocabularies of up to 1048576 tokens");
   if (g.ddd_enabled && g.temperature > 0.f)
     return fail(nullptr, AE_EUNSUPPORTED, "the DDD exit rule is implemented for greedy decoding only");
   if (g.n_ctx_max > kMaxSplits * kAttnChunk) return fail(nullptr, AE_EUNSUPPORTED, "n_ctx_max too large (<= 16384)");
@@ -506,7 +508,7 @@ int ae_init(const ae_config *cfg, const ae_weights *w, void *hip_stream, ae_ctx 
       (rc = dev_alloc(c, &c->attn_part, attn_part_floats(g))) || (rc = dev_alloc(c, &c->ldlp_u, (size_t)2 * d)) ||
       (rc = dev_alloc(c, &c->ldlp_z, (size_t)kMaxLdlpHidden)) ||
       (rc = dev_alloc(c, &c->hist, (size_t)g.n_ctx_max + 2)) || (rc = dev_alloc(c, &c->st, 1)) ||
-      (rc = dev_alloc(c, &c->prob, (size_t)4 * kMaxRows + 4)))
+      (rc = dev_alloc(c, &c->prob, sample_scratch_doubles(g.vocab))))
     return bail(rc);
   launch_rope_table(c->rope_tab, g.n_ctx_max, g.head_dim, g.rope_base, c->stream);
   launch_fill_zero(c->st, (sizeof(DevState) + 15) / 16 * 16, c->stream);

@@ -88,7 +88,7 @@ struct ae_ctx {
   float *amax_val = nullptr;       // LM-head argmax partials [vocab/16][16]
   int32_t *amax_idx = nullptr;
   int Pa = 0;                      // number of valid partial-sum rows in ssq_a
-  double *prob = nullptr;          // T>0 scratch [2][V]
+  double *prob = nullptr;          // T>0 scratch: segment / row statistics of the sampling kernels
   int32_t *hist = nullptr;         // device token history by slot
   ae::DevState *st = nullptr;      // device state
   ae::DevState *h_st = nullptr;    // pinned host mirror used for read-back / uploads
@@ -168,7 +168,8 @@ void launch_kv_export(const void *kv_layer, size_t v_off, const ae_config &c, in
 size_t attn_part_floats(const ae_config &c);
 
 // ---- T > 0 sampling (kernels_sample.hip) ----
-void launch_sample_draft(const float *logits, int V, float T, DevState *st, int i, double *prob, hipStream_t s);
+size_t sample_scratch_doubles(int V);   // size of the scratch both launches below take
+void launch_sample_draft(const float *logits, int V, float T, DevState *st, int i, double *scratch, hipStream_t s);
 void launch_accept_sample(const float *tl, const float *dl, int V, int k, float T, DevState *st, int32_t *hist,
                           int kv_len, double *prob, hipStream_t s);
 
