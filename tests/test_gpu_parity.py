@@ -263,20 +263,29 @@ def test_tiny_fp32_sampling_steps_match_oracle():
     eng.close()
 
 
-def test_bf16_sampling_kernels_match_oracle_rule_on_gpu_logits():
+def _sampling_cfgs():
+    from paper_2412_18910_amd.config import LLAMA_8B_GQA
+    return [(SMALL_BF16.with_(temperature=1.0), 16),
+            # the largest vocabulary of the workloads: 126 segments of 1024 tokens, the last one ragged
+            (LLAMA_8B_GQA.with_(n_layers=1, n_ctx_max=128, temperature=0.7), 6)]
+
+
+@pytest.mark.parametrize("cfg,n_steps", _sampling_cfgs(), ids=["small", "vocab128256"])
+def test_bf16_sampling_kernels_match_oracle_rule_on_gpu_logits(cfg, n_steps):
     """Accept-kernel parity: the oracle's rule applied to the logits the GPU produced must give
     the GPU's own (n_accepted, bonus) and draft samples, for the same uniforms."""
     import ctypes as C
     from oracle import binding as ob
+    from paper_2412_18910_amd.binding import Engine
+    from .gpu_helpers import to_device
     from .helpers import dp, fp, ip
-    cfg = SMALL_BF16.with_(temperature=1.0)
-    eng, orc, _ = make_pair(cfg, 9)
+    eng = Engine(cfg, to_device(synth.make_weights(cfg, 9)))
     lib = ob.load()
     ids = synth.token_ids(40, cfg.vocab, 91)
     eng.prefill(ids)
     V, T = cfg.vocab, float(cfg.temperature)
     n_acc_hist = []
-    for r in range(16):
+    for r in range(n_steps):
         k = 1 + r % cfg.k_max
         ud, ua = synth.uniforms(cfg.k_max, 3000 + r), synth.uniforms(cfg.k_max + 1, 4000 + r)
         d = eng.draft(k, u_draft=ud)
