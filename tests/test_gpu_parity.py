@@ -555,3 +555,30 @@ def test_ldlp_classification_head_matches_oracle(cfg0, seed):
         last_tok, f_row = (pend if ao[0] == 0 else int(d_o[ao[0] - 1])), ao[0]
     assert compared >= 3
     eng.close()
+
+
+def test_runs_are_bit_reproducible():
+    """No atomics on floating-point data and fixed reduction orders everywhere: two engines fed the
+    same bytes produce bit-identical logits, features and cache rows (dense prompt pass, greedy
+    steps, and a temperature > 0 configuration with the same uniforms)."""
+    from paper_2412_18910_amd.binding import Engine
+    from .gpu_helpers import to_device
+    for cfg in (MED_BF16, SMALL_BF16.with_(temperature=0.8)):
+        w = to_device(synth.make_weights(cfg, 40))
+        ids = synth.token_ids(130, cfg.vocab, 41)
+        runs = []
+        for rep in range(2):
+            eng = Engine(cfg, w)
+            eng.set_prefill_mode(Engine.PREFILL_DENSE)
+            eng.prefill(ids)
+            rec = [eng.logits(0).tobytes(), eng.kv_row(cfg.n_layers, 0, 100).tobytes()]
+            for r in range(4):
+                k = 2 + r
+                ud = synth.uniforms(cfg.k_max, 70 + r) if cfg.temperature > 0 else None
+                ua = synth.uniforms(cfg.k_max + 1, 80 + r) if cfg.temperature > 0 else None
+                kk, na, toks = eng.step(k_force=k, u_draft=ud, u_accept=ua)
+                rec += [toks.tobytes(), eng.logits(min(na, k)).tobytes(), eng.feature(0).tobytes(),
+                        eng.draft_logits(k - 1).tobytes()]
+            runs.append(rec)
+            eng.close()
+        assert runs[0] == runs[1]
