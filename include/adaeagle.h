@@ -102,8 +102,8 @@ const char *ae_last_error(const ae_ctx *ctx);
 
 /* First iteration of Algorithm 1 (k = 0, T = prompt): runs the n prompt tokens (host
  * ids) through the target and through the draft head for every slot whose next token is
- * known; leaves kv_len = n and pending = first new token.  Short prompts go through the
- * decode kernels in blocks of <= 16 rows; bf16 prompts of >= 64 tokens take the dense pass
+ * known; leaves kv_len = n and pending = first new token.  Prompts of up to 16 tokens go through
+ * the decode kernels as one block; longer bf16 prompts take the dense pass
  * (matrix-core bound GEMMs over chunks of up to chunk_rows rows, causal attention straight
  * off the cache; the draft head only needs its K/V rows there).  Both give the same state
  * up to rounding order. */

@@ -16,7 +16,7 @@ constexpr int kAttnChunk = 256;    // keys per split-KV workgroup (fixed by abso
 constexpr int kMaxSplits = 64;     // n_ctx_max / kAttnChunk upper bound
 constexpr int kMaxLdlpHidden = 1024;
 constexpr int kDenseRB = 8;        // activation row-blocks per workgroup of the dense prompt GEMM (128 rows)
-constexpr int kDenseMinPrompt = 64;   // shorter prompts go through the 16-row decode kernels
+constexpr int kDenseMinPrompt = 17;   // prompts of one 16-row block go through the decode kernels
 
 // Device-resident step state.  The host mirrors kv_len (it learns it at every accept).
 struct DevState {

@@ -88,15 +88,15 @@ def test_dense_and_block_prefill_agree_and_auto_picks_by_length():
     eng.prefill(ids)
     lb, fb = eng.logits(0), eng.feature(95 % 16)
     kb = eng.kv_row(cfg.n_layers, 0, 50)
-    eng.set_prefill_mode(Engine.PREFILL_AUTO)     # 96 >= 64 tokens: the dense pass
+    eng.set_prefill_mode(Engine.PREFILL_AUTO)     # more than one 16-row block: the dense pass
     eng.prefill(ids)
     ld, fd = eng.logits(0), eng.feature(95 % 16)
     kd = eng.kv_row(cfg.n_layers, 0, 50)
     assert np.max(np.abs(lb - ld)) <= TOL and np.max(np.abs(fb - fd)) <= 0.1
     assert np.max(np.abs(kb - kd)) <= np.max(np.abs(kb)) * 2 ** -7
     assert not np.array_equal(lb, ld)             # different kernels, different rounding order
-    # short prompts keep the 16-row path under AUTO: bit-identical to BLOCKS
-    short = synth.token_ids(40, cfg.vocab, 8)
+    # a prompt of one block keeps the 16-row path under AUTO: bit-identical to BLOCKS
+    short = synth.token_ids(16, cfg.vocab, 8)
     eng.prefill(short)
     la = eng.logits(0)
     eng.set_prefill_mode(Engine.PREFILL_BLOCKS)
