@@ -58,13 +58,20 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float *x, const floa
   __shared__ float red[4];
   const float *xr = x + (size_t)blockIdx.x * d;
   float ss = 0.f;
-  for (int i = threadIdx.x; i < d; i += 256) ss += xr[i] * xr[i];
+  for (int i = threadIdx.x * 4; i < d; i += 1024) {   // d is a multiple of 8
+    const float4 v = *reinterpret_cast<const float4 *>(xr + i);
+    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
   ss = wave_sum(ss);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
   __syncthreads();
   const float tot = (red[0] + red[1]) + (red[2] + red[3]);
   const float r = 1.0f / sqrtf(tot / (float)d + eps);
-  for (int i = threadIdx.x; i < d; i += 256) out[(size_t)blockIdx.x * d + i] = (xr[i] * r) * g[i];
+  for (int i = threadIdx.x * 4; i < d; i += 1024) {
+    const float4 v = *reinterpret_cast<const float4 *>(xr + i), gn = *reinterpret_cast<const float4 *>(g + i);
+    *reinterpret_cast<float4 *>(out + (size_t)blockIdx.x * d + i) =
+        make_float4((v.x * r) * gn.x, (v.y * r) * gn.y, (v.z * r) * gn.z, (v.w * r) * gn.w);
+  }
 }
 
 void launch_rmsnorm(const float *x, const float *g, int rows, int d, float eps, float *out, hipStream_t s) {
