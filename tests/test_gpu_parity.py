@@ -582,3 +582,30 @@ def test_runs_are_bit_reproducible():
             runs.append(rec)
             eng.close()
         assert runs[0] == runs[1]
+
+
+def test_largest_supported_context():
+    """n_ctx_max = 16384 is the largest cache the attention kernels accept (64 chunks of 256 keys):
+    a step right at the end of that cache, against the oracle; one slot more is refused."""
+    from paper_2412_18910_amd.binding import AE_EUNSUPPORTED, Engine
+    from .gpu_helpers import to_device
+    cfg = EDGE_BF16.with_(n_ctx_max=16384, k_max=7)
+    eng, orc, _ = make_pair(cfg, 23)
+    n = 16384 - 8 - 3                       # room for one 8-row block and a few accepted tokens
+    for layer in range(cfg.n_layers + 1):
+        k, v = synth.kv_fill(cfg, n, 77, layer)
+        orc.kv_import(layer, k, v)
+        eng.kv_import(layer, k, v)
+    feat = synth.feature_row(cfg, 24)
+    orc.set_state(n, 3, 4, feat)
+    eng.set_state(n, 3, 4, feat)
+    d_o = orc.draft(7)
+    assert np.array_equal(d_o, eng.draft(7, override_ids=d_o))
+    orc.verify(n_rows=8)
+    eng.verify(n_rows=8)
+    for row in range(8):
+        assert np.max(np.abs(orc.logits(row) - eng.logits(row))) <= 2e-2, row
+    eng.close()
+    with pytest.raises(AdaEagleError) as e:
+        Engine(cfg.with_(n_ctx_max=16385), to_device(synth.make_weights(cfg, 23)))
+    assert e.value.code == AE_EUNSUPPORTED
