@@ -14,7 +14,7 @@
 //    that two waves feed every matrix pipe; tiles are handed out XCD-aware; epilogues are
 //    those of the decode GEMM.
 //  * attn_prefill_kernel: causal flash attention straight off the tiled KV cache; a wave owns
-//    16 (row, head) pairs of one KV head and walks the visible keys 64 at a time with an
+//    32 (row, head) pairs of one KV head and walks the visible keys 32 at a time with an
 //    online softmax in the log2 domain; no partials, no merge, packed output.
 //  * embedding, 1/rms finalisation and the draft head's [feature ; embedding] input.
 #include "ae_internal.h"
@@ -307,130 +307,145 @@ void launch_draft_cat_dense(const float *x, int rows, int d, const float *gain, 
 // q: float [rows][H*HD] of the chunk (already rotated); chunk row i sits at slot pos0 + i and
 // sees slots 0..pos0+i of the tiled cache (which already holds the chunk's own K and V).
 // Pairs (row, query head of the KV head's group) are numbered r = row*G + head%G; a wave owns
-// 16 consecutive pairs, a workgroup 64; late (long) tiles are scheduled first.
-template <int HD>
+// MT tiles of 16 consecutive pairs and walks the visible keys 32 at a time: the K and V tiles
+// of a step (16 KB at head_dim 128) are loaded once and multiplied against all MT tiles, which
+// halves the cache traffic per MFMA against one tile per wave.  Late (long) tiles are
+// scheduled first.  No barriers, no LDS: every wave is independent.
+template <int HD, int MT>
 __global__ __launch_bounds__(256) void attn_prefill_kernel(const float *q, int rows, int pos0, int H, int Hkv, int n_ctx,
                                                            const u32x4 *Kc, const u32x4 *Vc, u32x4 *Xp_out, size_t kts,
                                                            float scale_log2e) {
   constexpr int DT = HD / 32, VT = HD / 16;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, g = lane >> 4, m = lane & 15;
   const int kh = blockIdx.x, G = H / Hkv, R = rows * G;
-  const int r0 = (((int)gridDim.y - 1 - (int)blockIdx.y) * 4 + w) * 16;
-  if (r0 >= R) return;   // wave-uniform; the kernel has no barriers
-  const int r = r0 + m;
-  const bool rok = r < R;
-  const int rr = rok ? r : R - 1;
-  const int row = rr / G, head = kh * G + rr % G;
-  const int limit = pos0 + row;                          // last slot this lane's row may see
-  const int last_key = pos0 + min(r0 + 15, R - 1) / G;   // last slot any row of the tile sees
-
-  u32x4 qh[DT], ql[DT];
+  const int r0 = (((int)gridDim.y - 1 - (int)blockIdx.y) * 4 + w) * (16 * MT);
+  if (r0 >= R) return;   // wave-uniform
+  int row[MT], head[MT], limit[MT];
+  bool rok[MT];
+  u32x4 qh[MT][DT], ql[MT][DT];
 #pragma unroll
-  for (int dt = 0; dt < DT; ++dt) {
-    const float *src = q + ((size_t)row * H + head) * HD + dt * 32 + g * 8;
-    const float4 a = *reinterpret_cast<const float4 *>(src), b = *reinterpret_cast<const float4 *>(src + 4);
-    uint32_t h0, h1, h2, h3, l0, l1, l2, l3;
-    split2(a.x * scale_log2e, a.y * scale_log2e, h0, l0);
-    split2(a.z * scale_log2e, a.w * scale_log2e, h1, l1);
-    split2(b.x * scale_log2e, b.y * scale_log2e, h2, l2);
-    split2(b.z * scale_log2e, b.w * scale_log2e, h3, l3);
-    qh[dt] = u32x4{h0, h1, h2, h3};
-    ql[dt] = u32x4{l0, l1, l2, l3};
+  for (int t = 0; t < MT; ++t) {
+    const int r = r0 + t * 16 + m;
+    rok[t] = r < R;
+    const int rr = rok[t] ? r : R - 1;
+    row[t] = rr / G;
+    head[t] = kh * G + rr % G;
+    limit[t] = pos0 + row[t];   // last slot this lane's row may see
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      const float *src = q + ((size_t)row[t] * H + head[t]) * HD + dt * 32 + g * 8;
+      const float4 a = *reinterpret_cast<const float4 *>(src), b = *reinterpret_cast<const float4 *>(src + 4);
+      uint32_t h0, h1, h2, h3, l0, l1, l2, l3;
+      split2(a.x * scale_log2e, a.y * scale_log2e, h0, l0);
+      split2(a.z * scale_log2e, a.w * scale_log2e, h1, l1);
+      split2(b.x * scale_log2e, b.y * scale_log2e, h2, l2);
+      split2(b.z * scale_log2e, b.w * scale_log2e, h3, l3);
+      qh[t][dt] = u32x4{h0, h1, h2, h3};
+      ql[t][dt] = u32x4{l0, l1, l2, l3};
+    }
+  }
+  const int last_key = pos0 + min(r0 + 16 * MT - 1, R - 1) / G;   // last slot any row of the wave sees
+
+  float mx[MT], lsum[MT];
+  f32x4 O[MT][VT];
+#pragma unroll
+  for (int t = 0; t < MT; ++t) {
+    mx[t] = -INFINITY;
+    lsum[t] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < VT; ++dt) O[t][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  float mx = -INFINITY, lsum = 0.f;
-  f32x4 O[VT];
-#pragma unroll
-  for (int dt = 0; dt < VT; ++dt) O[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  for (int kb = 0; kb <= last_key; kb += 64) {
-    u32x4 kreg[4][DT], vreg[2][VT];
+  for (int kb = 0; kb <= last_key; kb += 32) {
+    u32x4 kreg[2][DT], vreg[VT];
     const u32x4 *kp = Kc + (((size_t)kh * (n_ctx / 16) + (kb >> 4)) * DT) * 64 + lane;
 #pragma unroll
-    for (int kt = 0; kt < 4; ++kt)
+    for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) kreg[kt][dt] = kp[(kt * DT + dt) * 64];
     const u32x4 *vp = Vc + (((size_t)kh * (n_ctx / 32) + (kb >> 5)) * VT) * 64 + lane;
 #pragma unroll
-    for (int vb = 0; vb < 2; ++vb)
-#pragma unroll
-      for (int dt = 0; dt < VT; ++dt) vreg[vb][dt] = vp[(vb * VT + dt) * 64];
+    for (int dt = 0; dt < VT; ++dt) vreg[dt] = vp[dt * 64];
 
-    f32x4 S[4];
 #pragma unroll
-    for (int kt = 0; kt < 4; ++kt) S[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < MT; ++t) {
+      f32x4 S[2];
+      S[0] = f32x4{0.f, 0.f, 0.f, 0.f};
+      S[1] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) {
-#pragma unroll
-      for (int kt = 0; kt < 4; ++kt) S[kt] = mfma_bf16(kreg[kt][dt], qh[dt], S[kt]);
-#pragma unroll
-      for (int kt = 0; kt < 4; ++kt) S[kt] = mfma_bf16(kreg[kt][dt], ql[dt], S[kt]);
-    }
-    float bmax = -INFINITY;
-#pragma unroll
-    for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int key = kb + kt * 16 + 4 * g + e;
-        S[kt][e] = key <= limit ? S[kt][e] : -INFINITY;
-        bmax = fmaxf(bmax, S[kt][e]);
+      for (int dt = 0; dt < DT; ++dt) {
+        S[0] = mfma_bf16(kreg[0][dt], qh[t][dt], S[0]);
+        S[1] = mfma_bf16(kreg[1][dt], qh[t][dt], S[1]);
+        S[0] = mfma_bf16(kreg[0][dt], ql[t][dt], S[0]);
+        S[1] = mfma_bf16(kreg[1][dt], ql[t][dt], S[1]);
       }
-    bmax = fmaxf(bmax, __shfl_xor(bmax, 16, 64));
-    bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
-    const float mnew = fmaxf(mx, bmax);   // finite from the first block on: slot 0 is visible to every row
-    const float alpha = __builtin_amdgcn_exp2f(mx - mnew);
-    float bsum = 0.f;
+      float bmax = -INFINITY;
 #pragma unroll
-    for (int kt = 0; kt < 4; ++kt)
+      for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        S[kt][e] = __builtin_amdgcn_exp2f(S[kt][e] - mnew);
-        bsum += S[kt][e];
-      }
-    bsum += __shfl_xor(bsum, 16, 64);
-    bsum += __shfl_xor(bsum, 32, 64);
-    lsum = lsum * alpha + bsum;
-    mx = mnew;
+        for (int e = 0; e < 4; ++e) {
+          const int key = kb + kt * 16 + 4 * g + e;
+          S[kt][e] = key <= limit[t] ? S[kt][e] : -INFINITY;
+          bmax = fmaxf(bmax, S[kt][e]);
+        }
+      bmax = fmaxf(bmax, __shfl_xor(bmax, 16, 64));
+      bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
+      const float mnew = fmaxf(mx[t], bmax);   // finite from the first block on: slot 0 is visible to every row
+      const float alpha = __builtin_amdgcn_exp2f(mx[t] - mnew);
+      float bsum = 0.f;
 #pragma unroll
-    for (int dt = 0; dt < VT; ++dt) O[dt] *= alpha;
-    // P^T as B operand: k-slot e of lane group g = key 16*(e/4) + 4g + e%4 of a 32-key block
+      for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-    for (int vb = 0; vb < 2; ++vb) {
+        for (int e = 0; e < 4; ++e) {
+          S[kt][e] = __builtin_amdgcn_exp2f(S[kt][e] - mnew);
+          bsum += S[kt][e];
+        }
+      bsum += __shfl_xor(bsum, 16, 64);
+      bsum += __shfl_xor(bsum, 32, 64);
+      lsum[t] = lsum[t] * alpha + bsum;
+      mx[t] = mnew;
+#pragma unroll
+      for (int dt = 0; dt < VT; ++dt) O[t][dt] *= alpha;
+      // P^T as B operand: k-slot e of lane group g = key 16*(e/4) + 4g + e%4 of the 32-key block
       uint32_t h0, h1, h2, h3, l0, l1, l2, l3;
-      split2(S[2 * vb][0], S[2 * vb][1], h0, l0);
-      split2(S[2 * vb][2], S[2 * vb][3], h1, l1);
-      split2(S[2 * vb + 1][0], S[2 * vb + 1][1], h2, l2);
-      split2(S[2 * vb + 1][2], S[2 * vb + 1][3], h3, l3);
+      split2(S[0][0], S[0][1], h0, l0);
+      split2(S[0][2], S[0][3], h1, l1);
+      split2(S[1][0], S[1][1], h2, l2);
+      split2(S[1][2], S[1][3], h3, l3);
       const u32x4 ph = {h0, h1, h2, h3}, pl = {l0, l1, l2, l3};
 #pragma unroll
-      for (int dt = 0; dt < VT; ++dt) O[dt] = mfma_bf16(vreg[vb][dt], ph, O[dt]);
+      for (int dt = 0; dt < VT; ++dt) O[t][dt] = mfma_bf16(vreg[dt], ph, O[t][dt]);
 #pragma unroll
-      for (int dt = 0; dt < VT; ++dt) O[dt] = mfma_bf16(vreg[vb][dt], pl, O[dt]);
+      for (int dt = 0; dt < VT; ++dt) O[t][dt] = mfma_bf16(vreg[dt], pl, O[t][dt]);
     }
   }
-  if (rok) {
-    const float inv = 1.0f / lsum;
-    u32x4 *xp = Xp_out + (size_t)(row >> 4) * 128;
 #pragma unroll
-    for (int dt = 0; dt < VT; ++dt)
-      packed_store4(xp, row & 15, head * HD + dt * 16 + 4 * g, O[dt][0] * inv, O[dt][1] * inv, O[dt][2] * inv,
-                    O[dt][3] * inv, kts);
+  for (int t = 0; t < MT; ++t) {
+    if (rok[t]) {
+      const float inv = 1.0f / lsum[t];
+      u32x4 *xp = Xp_out + (size_t)(row[t] >> 4) * 128;
+#pragma unroll
+      for (int dt = 0; dt < VT; ++dt)
+        packed_store4(xp, row[t] & 15, head[t] * HD + dt * 16 + 4 * g, O[t][dt][0] * inv, O[t][dt][1] * inv,
+                      O[t][dt][2] * inv, O[t][dt][3] * inv, kts);
+    }
   }
 }
 
 void launch_attention_prefill(const float *q, int rows, int pos0, const ae_config &c, const void *kv_layer, size_t v_off,
                               void *Xp_out, int RB, hipStream_t s) {
+  constexpr int MT = 2;
   const int G = c.n_heads / c.n_kv_heads, R = rows * G, HD = c.head_dim;
-  const dim3 grid(c.n_kv_heads, (R + 63) / 64);
+  const dim3 grid(c.n_kv_heads, (R + 64 * MT - 1) / (64 * MT));
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)HD);
   const u32x4 *Kc = (const u32x4 *)kv_layer, *Vc = (const u32x4 *)((const char *)kv_layer + v_off);
   const int cap = kv_capacity(c);
   if (HD == 128)
-    attn_prefill_kernel<128><<<grid, 256, 0, s>>>(q, rows, pos0, c.n_heads, c.n_kv_heads, cap, Kc, Vc, (u32x4 *)Xp_out,
-                                                 (size_t)RB * 128, scale_log2e);
+    attn_prefill_kernel<128, MT><<<grid, 256, 0, s>>>(q, rows, pos0, c.n_heads, c.n_kv_heads, cap, Kc, Vc, (u32x4 *)Xp_out,
+                                                     (size_t)RB * 128, scale_log2e);
   else
-    attn_prefill_kernel<64><<<grid, 256, 0, s>>>(q, rows, pos0, c.n_heads, c.n_kv_heads, cap, Kc, Vc, (u32x4 *)Xp_out,
-                                                (size_t)RB * 128, scale_log2e);
+    attn_prefill_kernel<64, MT><<<grid, 256, 0, s>>>(q, rows, pos0, c.n_heads, c.n_kv_heads, cap, Kc, Vc, (u32x4 *)Xp_out,
+                                                    (size_t)RB * 128, scale_log2e);
 }
 
 }  // namespace ae
