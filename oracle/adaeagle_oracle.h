@@ -22,7 +22,8 @@
  * Eq. 3 round/clamp table, attention/RoPE/RMSNorm special cases, and a
  * float64 library re-expression of the whole forward at the tiny config.
  * Unpinned: behaviour of trained EAGLE/LDLP checkpoints (none available);
- * the draft-layer internals follow the readings listed in the design notes.
+ * the draft layer is a standard pre-norm Llama-style layer with both RMSNorms, an fc with bias
+ * over [feature ; embedding] and no norm on its output (the paper does not spell these out).
  */
 #ifndef ADAEAGLE_ORACLE_H
 #define ADAEAGLE_ORACLE_H
