@@ -70,3 +70,28 @@ def ldlp_loss(pred, truth, lam):
     truth = np.asarray(truth, np.float64)
     gap = truth - pred
     return float(np.mean(np.where(gap > 0, lam * gap, -gap))) if pred.size else 0.0
+
+
+def generate(engine, max_tokens, eos_id=None, u_stream=None):
+    """Algorithm 1 as a generation loop: after a prefill, repeat ae_step (LDLP -> draft ->
+    verify -> accept) until max_tokens tokens exist or the terminator eos_id was generated;
+    the output is cut right behind the terminator (tokens a step validated after it are
+    dropped).  Returns (tokens, Counters).  u_stream(step, n) supplies n uniforms for the
+    step's draws when the engine runs at temperature > 0 (draft draws first, then accept)."""
+    out = [int(engine.pending)]
+    cnt = Counters()
+    k_max = engine.cfg.k_max
+    step = 0
+    while len(out) < max_tokens and (eos_id is None or out[-1] != eos_id):
+        ud = ua = None
+        if u_stream is not None:
+            u = np.asarray(u_stream(step, 2 * k_max + 1), np.float64)
+            ud, ua = u[:k_max], u[k_max:]
+        k, na, toks = engine.step(u_draft=ud, u_accept=ua)
+        cnt.add(k, na)
+        for t in toks:
+            out.append(int(t))
+            if len(out) >= max_tokens or (eos_id is not None and int(t) == eos_id):
+                break
+        step += 1
+    return np.array(out, np.int64), cnt

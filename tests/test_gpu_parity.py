@@ -609,3 +609,23 @@ def test_largest_supported_context():
     with pytest.raises(AdaEagleError) as e:
         Engine(cfg.with_(n_ctx_max=16385), to_device(synth.make_weights(cfg, 23)))
     assert e.value.code == AE_EUNSUPPORTED
+
+
+def test_generate_until_terminator_matches_autoregressive_oracle():
+    """Alg. 1 end to end on the GPU (LDLP-chosen lengths, natural drafts, fp32): generation stops
+    right behind the first terminator and equals the oracle's plain greedy decoding up to there."""
+    from paper_2412_18910_amd.loop import generate
+    eng, orc, _ = make_pair(TINY, 0)
+    ids = synth.token_ids(64, TINY.vocab, 100)
+    orc.prefill(ids)
+    ref = [int(orc.pending)] + [int(t) for t in orc.ar_greedy(90)]
+    eos = ref[40]
+    cut = ref.index(eos) + 1
+    eng.prefill(ids)
+    toks, cnt = generate(eng, 200, eos_id=eos)
+    assert list(toks) == ref[:cut]
+    assert cnt.tokens >= cut - 1 and cnt.n_target >= 1
+    eng.prefill(ids)
+    toks, _ = generate(eng, 33)                      # no terminator: the token budget ends it
+    assert list(toks) == ref[:33]
+    eng.close()

@@ -7,7 +7,7 @@ import numpy as np
 
 from paper_2412_18910_amd import synth
 from paper_2412_18910_amd.config import LLAMA_13B, LLAMA_7B, LLAMA_8B_GQA, TINY
-from paper_2412_18910_amd.loop import Counters, run_scripted, scripted_override
+from paper_2412_18910_amd.loop import Counters, generate, run_scripted, scripted_override
 from paper_2412_18910_amd.prefill_bench import model_flops
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -122,3 +122,36 @@ def test_prompt_pass_flops():
     attn = 4 * c.n_layers * c.d_model * n * (n + 1) // 2
     assert model_flops(c, n) == 2 * n * (c.n_layers * per_layer + draft) + attn
     assert 26e12 < model_flops(c, n) < 29e12
+
+
+class _ScriptedEngine:
+    """Emits a fixed token sequence in steps of varying size, like an engine after prefill."""
+
+    def __init__(self, seq, sizes):
+        self.seq, self.sizes, self.pos, self.i = list(seq), sizes, 1, 0
+        self.pending = seq[0]
+
+        class _C:
+            k_max = 8
+        self.cfg = _C()
+
+    def step(self, u_draft=None, u_accept=None):
+        n = self.sizes[self.i % len(self.sizes)]
+        self.i += 1
+        toks = np.array(self.seq[self.pos:self.pos + n], np.int32)
+        self.pos += n
+        return n + 1, n - 1, toks
+
+
+def test_generate_stops_at_the_terminator_or_the_budget():
+    """Alg. 1 runs until a terminator is generated; the output ends right behind it even when the
+    step that produced it validated more tokens."""
+    seq = list(range(100, 160))
+    toks, cnt = generate(_ScriptedEngine(seq, [3, 1, 4]), 20)
+    assert list(toks) == seq[:20]
+    toks, cnt = generate(_ScriptedEngine(seq, [3, 1, 4]), 50, eos_id=106)     # 106 sits mid-step
+    assert list(toks) == seq[:7] and toks[-1] == 106 and cnt.n_target == 3
+    toks, _ = generate(_ScriptedEngine(seq, [3, 1, 4]), 50, eos_id=100)       # the first token already ends it
+    assert list(toks) == [100]
+    toks, _ = generate(_ScriptedEngine(seq, [2]), 9, eos_id=999)              # never generated: the budget ends it
+    assert list(toks) == seq[:9]
