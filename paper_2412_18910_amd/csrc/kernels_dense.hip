@@ -356,37 +356,54 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const float *q, int r
     for (int dt = 0; dt < VT; ++dt) O[t][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  for (int kb = 0; kb <= last_key; kb += 32) {
-    u32x4 kreg[2][DT], vreg[VT];
+  // K and V tiles of a step live in registers; the K tiles of the next step are requested as soon as
+  // this step's scores are done and the V tiles as soon as its P.V products are issued, so the loads
+  // fly behind the softmax / MFMA work instead of in front of it (no extra registers).
+  u32x4 kreg[2][DT], vreg[VT];
+  auto load_k = [&](int kb) {
     const u32x4 *kp = Kc + (((size_t)kh * (n_ctx / 16) + (kb >> 4)) * DT) * 64 + lane;
 #pragma unroll
     for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) kreg[kt][dt] = kp[(kt * DT + dt) * 64];
+  };
+  auto load_v = [&](int kb) {
     const u32x4 *vp = Vc + (((size_t)kh * (n_ctx / 32) + (kb >> 5)) * VT) * 64 + lane;
 #pragma unroll
     for (int dt = 0; dt < VT; ++dt) vreg[dt] = vp[dt * 64];
-
+  };
+  load_k(0);
+  load_v(0);
+  const int last_kb = last_key & ~31;
+  for (int kb = 0; kb <= last_key; kb += 32) {
+    const int kb_next = min(kb + 32, last_kb);   // the last step re-requests its own tiles (ignored)
+    f32x4 S[MT][2];
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
-      f32x4 S[2];
-      S[0] = f32x4{0.f, 0.f, 0.f, 0.f};
-      S[1] = f32x4{0.f, 0.f, 0.f, 0.f};
+      S[t][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+      S[t][1] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
-        S[0] = mfma_bf16(kreg[0][dt], qh[t][dt], S[0]);
-        S[1] = mfma_bf16(kreg[1][dt], qh[t][dt], S[1]);
-        S[0] = mfma_bf16(kreg[0][dt], ql[t][dt], S[0]);
-        S[1] = mfma_bf16(kreg[1][dt], ql[t][dt], S[1]);
+        S[t][0] = mfma_bf16(kreg[0][dt], qh[t][dt], S[t][0]);
+        S[t][1] = mfma_bf16(kreg[1][dt], qh[t][dt], S[t][1]);
+        S[t][0] = mfma_bf16(kreg[0][dt], ql[t][dt], S[t][0]);
+        S[t][1] = mfma_bf16(kreg[1][dt], ql[t][dt], S[t][1]);
       }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    load_k(kb_next);
+    __builtin_amdgcn_sched_barrier(0);
+    u32x4 ph[MT], pl[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
       float bmax = -INFINITY;
 #pragma unroll
       for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int key = kb + kt * 16 + 4 * g + e;
-          S[kt][e] = key <= limit[t] ? S[kt][e] : -INFINITY;
-          bmax = fmaxf(bmax, S[kt][e]);
+          S[t][kt][e] = key <= limit[t] ? S[t][kt][e] : -INFINITY;
+          bmax = fmaxf(bmax, S[t][kt][e]);
         }
       bmax = fmaxf(bmax, __shfl_xor(bmax, 16, 64));
       bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
@@ -397,8 +414,8 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const float *q, int r
       for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          S[kt][e] = __builtin_amdgcn_exp2f(S[kt][e] - mnew);
-          bsum += S[kt][e];
+          S[t][kt][e] = __builtin_amdgcn_exp2f(S[t][kt][e] - mnew);
+          bsum += S[t][kt][e];
         }
       bsum += __shfl_xor(bsum, 16, 64);
       bsum += __shfl_xor(bsum, 32, 64);
@@ -408,16 +425,23 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(const float *q, int r
       for (int dt = 0; dt < VT; ++dt) O[t][dt] *= alpha;
       // P^T as B operand: k-slot e of lane group g = key 16*(e/4) + 4g + e%4 of the 32-key block
       uint32_t h0, h1, h2, h3, l0, l1, l2, l3;
-      split2(S[0][0], S[0][1], h0, l0);
-      split2(S[0][2], S[0][3], h1, l1);
-      split2(S[1][0], S[1][1], h2, l2);
-      split2(S[1][2], S[1][3], h3, l3);
-      const u32x4 ph = {h0, h1, h2, h3}, pl = {l0, l1, l2, l3};
-#pragma unroll
-      for (int dt = 0; dt < VT; ++dt) O[t][dt] = mfma_bf16(vreg[dt], ph, O[t][dt]);
-#pragma unroll
-      for (int dt = 0; dt < VT; ++dt) O[t][dt] = mfma_bf16(vreg[dt], pl, O[t][dt]);
+      split2(S[t][0][0], S[t][0][1], h0, l0);
+      split2(S[t][0][2], S[t][0][3], h1, l1);
+      split2(S[t][1][0], S[t][1][1], h2, l2);
+      split2(S[t][1][2], S[t][1][3], h3, l3);
+      ph[t] = u32x4{h0, h1, h2, h3};
+      pl[t] = u32x4{l0, l1, l2, l3};
     }
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+#pragma unroll
+      for (int dt = 0; dt < VT; ++dt) O[t][dt] = mfma_bf16(vreg[dt], ph[t], O[t][dt]);
+#pragma unroll
+      for (int dt = 0; dt < VT; ++dt) O[t][dt] = mfma_bf16(vreg[dt], pl[t], O[t][dt]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    load_v(kb_next);
+    __builtin_amdgcn_sched_barrier(0);
   }
 #pragma unroll
   for (int t = 0; t < MT; ++t) {
