@@ -73,6 +73,24 @@ def test_worked_example_accept_probabilities_and_residual(orc):
     np.testing.assert_allclose(law, P, atol=2e-3)
 
 
+def test_token_the_target_excludes_is_never_accepted(orc):
+    """Sec. 2.1: acceptance probability min(1, p/p_hat) is 0 when the target gives the token no mass;
+    the strict comparison u < ratio rejects it even for u = 0, and the replacement comes from the
+    target (the residual max(0, p - p_hat) has no mass on the rejected token)."""
+    V = 6
+    tl = np.zeros((2, V), np.float32)
+    tl[0, 2] = -5000.0                           # exp underflows: p(2) = 0 exactly
+    dl = np.zeros((1, V), np.float32)
+    dl[0, 2] = 5.0                               # the draft is confident in token 2
+    for u1 in (0.0, 0.3, 0.999):
+        na, b = _sample(orc, tl, dl, [2], 1.0, [0.0, u1])
+        assert na == 0 and b != 2
+    # with any target mass at all and u = 0 it is accepted
+    tl[0, 2] = -20.0
+    na, _ = _sample(orc, tl, dl, [2], 1.0, [0.0, 0.5])
+    assert na == 1
+
+
 def test_all_accepted_bonus_follows_target_row_k(orc):
     tl = np.log(np.array([[0.25, 0.25, 0.5], [0.1, 0.6, 0.3]]))
     dl = tl[:1]

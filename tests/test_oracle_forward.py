@@ -91,6 +91,47 @@ def test_draft_head_matches_float64_library():
     x2 = torch.cat([fh[-1], w["tok_emb"].double()[int(got2[0])]]) @ w["draft_fc_w"].double().T + w["draft_fc_b"].double()
     fh2 = _layer64(cfg, w["draft_layer"], torch.cat([x, x2[None]]), torch.arange(21))
     np.testing.assert_allclose(m2.draft_logits(1), (fh2[-1] @ w["lm_head"].double().T).numpy(), atol=2e-5, rtol=0)
+    # third token: chained from the second token and the second output, not from the first
+    m3, _ = make_oracle(cfg, 0)
+    m3.prefill(ids)
+    forced = np.array([int(got2[0]), (int(got2[0]) + 1234) % cfg.vocab, -1], np.int32)
+    got3 = m3.draft(3, override_ids=forced)
+    assert list(got3[:2]) == list(forced[:2])
+    x2b = torch.cat([fh[-1], w["tok_emb"].double()[int(forced[0])]]) @ w["draft_fc_w"].double().T + w["draft_fc_b"].double()
+    fh2b = _layer64(cfg, w["draft_layer"], torch.cat([x, x2b[None]]), torch.arange(21))
+    x3 = torch.cat([fh2b[-1], w["tok_emb"].double()[int(forced[1])]]) @ w["draft_fc_w"].double().T + w["draft_fc_b"].double()
+    fh3 = _layer64(cfg, w["draft_layer"], torch.cat([x, x2b[None], x3[None]]), torch.arange(22))
+    np.testing.assert_allclose(m3.draft_logits(2), (fh3[-1] @ w["lm_head"].double().T).numpy(), atol=3e-5, rtol=0)
+
+
+def test_draft_catch_up_over_several_rows_hands_on_the_last_row():
+    """Eq. 2 after a step that validated tokens: the head first recomputes the slots of the accepted
+    tokens from their true features; its next-token logits come from the LAST of those rows."""
+    cfg = TINY
+    m, w = make_oracle(cfg, 0)
+    ids = synth.token_ids(20, cfg.vocab, 21)
+    ar, _ = make_oracle(cfg, 0, weights=w)
+    ar.prefill(ids)
+    t1 = ar.pending
+    t234 = ar.ar_greedy(3)                       # tokens after t1 under the target alone
+    m.prefill(ids)
+    m.draft(2, override_ids=t234[:2])             # a draft the target will accept in full
+    m.verify(n_rows=3)
+    na, bonus = m.accept()
+    assert (na, bonus) == (2, int(t234[2]))
+    m.draft(1)                                    # catch-up over slots 20, 21, 22, then one token
+    seq = np.concatenate([ids, [t1], t234])       # 24 tokens; slot s pairs feature s with token s + 1
+    F64, _ = _target64(cfg, w, seq[:23])
+    emb = w["tok_emb"].double()[torch.as_tensor(seq[1:24]).long()]
+    x = torch.cat([F64, emb], -1) @ w["draft_fc_w"].double().T + w["draft_fc_b"].double()
+    fh = _layer64(cfg, w["draft_layer"], x, torch.arange(23))
+    want = (fh[-1] @ w["lm_head"].double().T).numpy()
+    np.testing.assert_allclose(m.draft_logits(0), want, atol=3e-5, rtol=0)
+    wrong = (fh[-3] @ w["lm_head"].double().T).numpy()   # the first catch-up row would give this
+    assert np.max(np.abs(wrong - want)) > 1e-2
+    # the sequence log-probability starts afresh with every draft
+    lp = torch.log_softmax(torch.from_numpy(m.draft_logits(0)).double(), -1)
+    assert abs(m.draft_logprob - float(lp.max())) < 1e-6
 
 
 @pytest.mark.parametrize("cfg", [TINY, SMALL_BF16], ids=["tiny-fp32", "small-bf16-gqa"])
@@ -152,6 +193,12 @@ def test_bf16_cache_rows_are_bf16_values():
         row = m.kv_row(1, which, 5)
         assert np.array_equal(row, torch.from_numpy(row).bfloat16().float().numpy())
         assert np.any(row != 0)
+    # rows installed from outside are held to the same 8 significant bits (round to nearest even)
+    k = np.random.default_rng(3).standard_normal((4, cfg.n_kv_heads * cfg.head_dim)).astype(np.float32)
+    m.kv_import(0, k, -k)
+    want = torch.from_numpy(k).bfloat16().float().numpy()
+    assert np.any(want != k)
+    assert np.array_equal(m.kv_row(0, 0, 2), want[2]) and np.array_equal(m.kv_row(0, 1, 3), -want[3])
 
 
 def test_kv_import_and_set_state_reproduce_prefill_state():

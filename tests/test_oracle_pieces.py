@@ -175,3 +175,7 @@ def test_inverse_cdf_table(orc):
         assert orc.orc_sample_inverse_cdf(dp(q), 5, u) == want
     q2 = q * 7.5  # unnormalised input gives the same answer
     assert orc.orc_sample_inverse_cdf(dp(q2), 5, 0.69) == 3
+    # u so close to 1 that u * total rounds to the total: the draw must still carry mass
+    q3 = np.array([0.25, 0.75, 0.0, 0.0], np.float64)
+    for u in (1.0, float(np.nextafter(1.0, 0.0))):
+        assert orc.orc_sample_inverse_cdf(dp(q3), 4, u) == 1

@@ -225,6 +225,55 @@ def test_ddd_keeps_the_longer_of_the_two_lengths():
     assert len(m5.draft(0)) == 1
 
 
+def test_ddd_equality_with_the_threshold_continues():
+    """Sec. 4.1: the AdaEAGLE-DDD exit needs the sequence probability to be LOWER than the threshold.
+    With a one-token vocabulary every draft sequence has probability exactly 1 (log 0): at
+    threshold 0 nothing is lower, the draft runs to k_max; any threshold above 0 ends it at k."""
+    cfg = TINY.with_(vocab=1, ddd_enabled=1, ddd_threshold=0.0)
+    m, w = make_oracle(cfg, 0)
+    m.prefill(np.zeros(8, np.int32))
+    assert len(m.draft(2)) == cfg.k_max and m.draft_logprob == 0.0
+    m2, _ = make_oracle(cfg.with_(ddd_threshold=1e-6), 0, weights=w)
+    m2.prefill(np.zeros(8, np.int32))
+    assert len(m2.draft(2)) == 2
+
+
+def test_sampled_and_overridden_draft_tokens_and_their_logprob():
+    """The draft token at temperature T is the inverse-CDF draw from softmax(logits / T) with the
+    caller's uniform, and the DDD statistic is the log-probability of the tokens actually chained
+    (drawn or overridden) under that same law -- not of the most likely ones."""
+    T = 0.7
+    cfg = TINY.with_(temperature=T, ddd_enabled=1, ddd_threshold=-1e9)
+    m, w = make_oracle(cfg, 0)
+    ids = synth.token_ids(24, cfg.vocab, 300)
+    m.prefill(ids)
+    u = np.random.default_rng(5).random(cfg.k_max)
+    got = m.draft(2, u_draft=u)
+    assert len(got) == cfg.k_max
+    want_lp, n_off_mode = 0.0, 0
+    for i, t in enumerate(got):
+        z = m.draft_logits(i).astype(np.float64) / T
+        p = np.exp(z - z.max())
+        c = np.cumsum(p)
+        assert int(t) == int(np.searchsorted(c, u[i] * c[-1], side="right"))
+        want_lp += z[int(t)] - z.max() - np.log(c[-1])
+        n_off_mode += int(t) != int(z.argmax())
+    assert n_off_mode >= 1                       # the draws really left the mode
+    assert abs(m.draft_logprob - want_lp) < 1e-6
+    # greedy head, tokens forced by the caller: their log-probability, not the mode's
+    cfg0 = TINY.with_(ddd_enabled=1, ddd_threshold=-1e9)
+    m0, _ = make_oracle(cfg0, 0, weights=w)
+    m0.prefill(ids)
+    forced = np.array([7, 7, 1900, 3, -1, -1, 42, 0], np.int32)[:cfg.k_max]
+    got0 = m0.draft(0, override_ids=forced)
+    want0 = 0.0
+    for i, t in enumerate(got0):
+        lp = torch.log_softmax(torch.from_numpy(m0.draft_logits(i)).double(), -1)
+        assert int(t) == (int(forced[i]) if forced[i] >= 0 else int(lp.argmax()))
+        want0 += float(lp[int(t)])
+    assert abs(m0.draft_logprob - want0) < 1e-6
+
+
 def test_ddd_run_stays_lossless(ar_reference):
     ids, w, _, ar = ar_reference
     cfg = TINY.with_(ddd_enabled=1, ddd_threshold=-8.0)
@@ -266,7 +315,8 @@ def test_ldlp_classification_closed_form_and_ties():
     w["ldlp_w_out"] = torch.ones_like(w["ldlp_w_out"])
     ids = synth.token_ids(8, cfg.vocab, 5)
     s = 0.5 / (1 + np.exp(-0.5)) * cfg.ldlp_hidden
-    for bias, want_k in (([0, 0, 0, 0, 0, 3, 0, 0, 0], 5), ([1, 0, 0, 2, 0, 2, 0, 0, 1], 3), ([0] * 9, 0)):
+    for bias, want_k in (([0, 0, 0, 0, 0, 3, 0, 0, 0], 5), ([1, 0, 0, 2, 0, 2, 0, 0, 1], 3), ([0] * 9, 0),
+                         ([0, 0, 0, 0, 0, 0, 0, 1, 2], 8)):   # k_max itself is a class
         w["ldlp_b_out"] = torch.tensor(bias, dtype=torch.float32)
         m, _ = make_oracle(cfg, 0, weights=w)
         m.prefill(ids)
