@@ -7,6 +7,7 @@ from paper_2412_18910_amd.binding import AE_EINVAL, AE_ESTATE, AdaEagleError
 from paper_2412_18910_amd.config import BF16, FP32, Config, TINY
 
 from .gpu_helpers import make_pair, top2_margin
+from .helpers import make_oracle
 
 pytestmark = pytest.mark.gpu
 
@@ -20,16 +21,24 @@ MARGIN = 5e-2
 def run_teacher_forced(cfg, seed, prompt_len, n_steps, script_mean=2.5):
     """Both sides get the same ids at every step; logits, features, LDLP scalar, draft
     logits, accepted lengths and tokens are compared step by step."""
-    eng, orc, _ = make_pair(cfg, seed)
+    eng, orc, w = make_pair(cfg, seed)
     ids = synth.token_ids(prompt_len, cfg.vocab, seed + 100)
     orc.prefill(ids)
     eng.prefill(ids)
     tol = TOL[cfg.dtype]
     assert eng.kv_len == orc.kv_len == prompt_len
     assert eng.pending == orc.pending
+    # Acceptance is scripted (a random-init head is almost never accepted on its own): the first
+    # a draft tokens of a step are the target's own next tokens, the next one is guaranteed wrong,
+    # so the steps that follow start from several validated rows (multi-row draft catch-up,
+    # LDLP on the last accepted token) on both sides.
     script = synth.truncated_geometric(n_steps, script_mean, cfg.k_max, seed + 7)
+    ar_orc, _ = make_oracle(cfg, seed, weights=w)
+    ar_orc.prefill(ids)
+    formal = np.concatenate([[ar_orc.pending], ar_orc.ar_greedy(n_steps * (cfg.k_max + 1) + 1)])
+    pos = 1                                   # formal[pos] = token that follows the pending one
     worst = 0.0
-    stats = dict(steps=0, submargin=0)
+    stats = dict(steps=0, submargin=0, accepted=0)
     for r in range(n_steps):
         ko, yo = orc.ldlp()
         kg, yg = eng.ldlp()
@@ -37,7 +46,12 @@ def run_teacher_forced(cfg, seed, prompt_len, n_steps, script_mean=2.5):
         if abs(yo - (np.floor(yo) + 0.5)) > 1e-2:
             assert ko == kg
         k = ko
-        d_o = orc.draft(k)
+        a = min(int(script[r]), k)
+        ov = -np.ones(max(k, 1), np.int32)
+        ov[:a] = formal[pos:pos + a]
+        if a < k:
+            ov[a] = (int(formal[pos + a]) + 1) % cfg.vocab
+        d_o = orc.draft(k, override_ids=ov[:k] if k else None)
         # the GPU drafts freely; its tokens must equal the oracle's wherever the oracle's
         # draft logits have a clear winner; afterwards it is re-run teacher-forced
         d_g = eng.draft(k, override_ids=d_o)
@@ -45,7 +59,7 @@ def run_teacher_forced(cfg, seed, prompt_len, n_steps, script_mean=2.5):
             lo, lg = orc.draft_logits(i), eng.draft_logits(i)
             worst = max(worst, float(np.max(np.abs(lo - lg))))
             assert np.max(np.abs(lo - lg)) <= tol, (r, i)
-            if top2_margin(lo) > MARGIN:
+            if ov[i] < 0 and top2_margin(lo) > MARGIN:   # a token the head chose itself
                 assert int(np.argmax(lg)) == int(d_o[i])
         assert np.array_equal(d_g, d_o)
         orc.verify(n_rows=k + 1)
@@ -60,8 +74,11 @@ def run_teacher_forced(cfg, seed, prompt_len, n_steps, script_mean=2.5):
         na_o, b_o = orc.accept()
         na_g, b_g = eng.accept()
         stats["steps"] += 1
+        stats["accepted"] += na_o
+        pos += na_o + 1
         if clear:
             assert (na_g, b_g) == (na_o, b_o), r
+            assert na_o == a and b_o == int(formal[pos - 1]), r
         elif (na_g, b_g) != (na_o, b_o):
             stats["submargin"] += 1
             break   # the two sequences legitimately part ways on a sub-margin row
@@ -72,7 +89,7 @@ def run_teacher_forced(cfg, seed, prompt_len, n_steps, script_mean=2.5):
 
 def test_tiny_fp32_teacher_forced_steps():
     worst, st = run_teacher_forced(TINY, 0, 64, 24)
-    assert st["submargin"] == 0
+    assert st["submargin"] == 0 and st["accepted"] >= 24
     assert worst < 1e-4
 
 
@@ -186,6 +203,20 @@ def test_kv_import_and_set_state_round_trip():
         if layer in (0, cfg.n_layers):
             assert np.array_equal(eng.kv_row(layer, 0, 517), k[517])
             assert np.array_equal(eng.kv_row(layer, 1, 3), v[3])
+    # values with more than 8 significant bits are rounded to nearest even on the way in, both sides
+    rng = np.random.default_rng(11)
+    k2 = rng.standard_normal((8, cfg.n_kv_heads * cfg.head_dim)).astype(np.float32)
+    k2[0, :4] = [1.00390625, 1.01171875, -1.00390625, 3.0e-39]      # two ties (to even), a negative tie, a subnormal
+    scratch = cfg.n_layers                                            # the draft layer's cache, re-imported below
+    orc.kv_import(scratch, k2, -k2)
+    eng.kv_import(scratch, k2, -k2)
+    for slot in (0, 5):
+        assert np.array_equal(eng.kv_row(scratch, 0, slot), orc.kv_row(scratch, 0, slot))
+        assert np.array_equal(eng.kv_row(scratch, 1, slot), orc.kv_row(scratch, 1, slot))
+    assert list(orc.kv_row(scratch, 0, 0)[:3]) == [1.0, 1.015625, -1.0]
+    k, v = synth.kv_fill(cfg, n, 9, scratch)
+    orc.kv_import(scratch, k, v)
+    eng.kv_import(scratch, k, v)
     feat = synth.feature_row(cfg, 5)
     orc.set_state(n, 17, 23, feat)
     eng.set_state(n, 17, 23, feat)
@@ -255,6 +286,9 @@ def test_tiny_fp32_sampling_steps_match_oracle():
     for r in range(24):
         k = orc.ldlp()[0] if r % 3 else (r // 3) % (cfg.k_max + 1)
         ud, ua = synth.uniforms(cfg.k_max, 1000 + r), synth.uniforms(cfg.k_max + 1, 2000 + r)
+        if r in (7, 16):      # uniforms at the two ends of [0, 1): first / last token that carries mass
+            edge = 0.0 if r == 7 else float(np.nextafter(1.0, 0.0))
+            ud, ua = np.full_like(ud, edge), np.full_like(ua, edge)
         ko, nao, to = orc.step(k_force=k, u_draft=ud, u_accept=ua)
         kg, nag, tg = eng.step(k_force=k, u_draft=ud, u_accept=ua)
         assert (ko, nao) == (kg, nag) and np.array_equal(to, tg), r
@@ -444,9 +478,29 @@ def test_ddd_exit_rule_matches_oracle(cfg0, seed):
         eng.verify(n_rows=len(got) + 1)
         lo, lg = orc.logits(len(want)), eng.logits(len(got))
         assert np.max(np.abs(lo - lg)) <= TOL[cfg.dtype]
-        if all(top2_margin(orc.logits(r)) > MARGIN for r in range(len(want) + 1)):
-            assert orc.accept() == eng.accept()
+        clear = all(top2_margin(orc.logits(r)) > MARGIN for r in range(len(want) + 1))
+        acc_o, acc_g = orc.accept(), eng.accept()
+        assert acc_o == acc_g or not clear
+        if acc_o == acc_g:
+            # next step: the statistic starts from zero again
+            w2 = orc.draft(1)
+            g2 = eng.draft(1, override_ids=np.concatenate([w2, -np.ones(cfg.k_max, np.int32)])[:cfg.k_max])
+            assert np.array_equal(w2, g2)
+            assert abs(orc.draft_logprob - eng.draft_logprob) < (1e-3 if cfg0.dtype == FP32 else 5e-2)
         eng.close()
+    # tokens forced by the caller: the statistic is the log-probability of THOSE tokens, on both sides
+    cfg = cfg0.with_(ddd_enabled=1, ddd_threshold=-1e9)      # never reached: k_max tokens, no decision near a tie
+    eng, orc, _ = make_pair(cfg, seed)
+    orc.prefill(ids)
+    eng.prefill(ids)
+    forced = -np.ones(cfg.k_max, np.int32)
+    forced[:3] = [5, (int(d_o[1]) + 77) % cfg.vocab, 9]
+    want = orc.draft(1, override_ids=forced)
+    got = eng.draft(1, override_ids=np.where(forced >= 0, forced, np.concatenate([want, forced])[:cfg.k_max]))
+    assert np.array_equal(want, got) and list(want[:3]) == list(forced[:3]) and len(want) == cfg.k_max
+    assert orc.draft_logprob < -10.0       # three unlikely tokens
+    assert abs(orc.draft_logprob - eng.draft_logprob) < (1e-3 if cfg0.dtype == FP32 else 0.1)
+    eng.close()
 
 
 EDGE_BF16 = Config(2, 256, 4, 2, 64, 512, 1024, dtype=BF16, k_max=15, n_ctx_max=1024, ldlp_hidden=64)
@@ -555,6 +609,30 @@ def test_ldlp_classification_head_matches_oracle(cfg0, seed):
         last_tok, f_row = (pend if ao[0] == 0 else int(d_o[ao[0] - 1])), ao[0]
     assert compared >= 3
     eng.close()
+
+
+def test_ldlp_classification_reaches_every_length_including_k_max():
+    """Zero input layer and equal output rows: the bias alone names the class, on both sides."""
+    import torch
+    from paper_2412_18910_amd.binding import Engine
+    from .gpu_helpers import to_device
+    cfg = TINY.with_(ldlp_cls=1)
+    w = dict(synth.make_weights(cfg, 0))
+    w["ldlp_w_in"] = torch.zeros_like(w["ldlp_w_in"])
+    w["ldlp_b_in"] = torch.full_like(w["ldlp_b_in"], 0.5)
+    w["ldlp_w_out"] = torch.ones_like(w["ldlp_w_out"])
+    ids = synth.token_ids(8, cfg.vocab, 5)
+    for want_k in (0, 3, cfg.k_max):
+        bias = torch.zeros(cfg.k_max + 1)
+        bias[want_k] = 2.0
+        w["ldlp_b_out"] = bias
+        orc, _ = make_oracle(cfg, 0, weights=w)
+        eng = Engine(cfg, to_device(w))
+        orc.prefill(ids)
+        eng.prefill(ids)
+        (ko, yo), (kg, yg) = orc.ldlp(), eng.ldlp()
+        assert ko == kg == want_k and abs(yo - yg) < 1e-3
+        eng.close()
 
 
 def test_runs_are_bit_reproducible():
