@@ -49,6 +49,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prompt-pass timing")
+    ap.add_argument("--temperature", type=float, default=0.0,
+                    help="> 0: rejection sampling with seeded uniforms and the natural acceptance of the random-init "
+                         "draft head instead of the greedy loop under scripted acceptance")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run 4 plain device copies of 512 MiB (counter calibration under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -66,7 +69,8 @@ def main():
 
     K, W = args.steps, args.warmup
     n_formal = (2 * K + W + 2) * 9 + 64
-    cfg = PRESETS[args.preset].with_(temperature=0.0)
+    T = args.temperature
+    cfg = PRESETS[args.preset].with_(temperature=T)
     cfg = cfg.with_(n_ctx_max=args.context + n_formal + 64)
     dev = "cuda:0"
     torch.cuda.set_device(0)
@@ -79,54 +83,91 @@ def main():
     def sync():
         torch.cuda.synchronize()
 
-    # ---- plain autoregressive decoding on the same kernels: formal sequence + AR baseline
-    eng.prefill(ctx_ids)
-    first = eng.pending
-    formal = np.zeros(n_formal, np.int64)
-    n_ar_timed = min(128, n_formal - 8)
-    for i in range(8):
-        eng.verify([eng.pending]); formal[i] = eng.accept()[1]
-    sync(); t0 = time.perf_counter()
-    for i in range(8, 8 + n_ar_timed):
-        eng.verify([eng.pending]); formal[i] = eng.accept()[1]
-    sync(); ar_s = time.perf_counter() - t0
-    for i in range(8 + n_ar_timed, n_formal):
-        eng.verify([eng.pending]); formal[i] = eng.accept()[1]
-    ar_tok_s = n_ar_timed / ar_s
+    if T > 0:
+        # ---- temperature > 0: tokens are drawn (inverse CDF, seeded uniforms); the draft head's own acceptance
+        def u(n, seed):
+            return synth.uniforms(n, seed)
+        eng.prefill(ctx_ids)
+        for i in range(8):
+            eng.verify([eng.pending]); eng.accept(u(1, 50 + i))
+        n_ar_timed = 128
+        sync(); t0 = time.perf_counter()
+        for i in range(n_ar_timed):
+            eng.verify([eng.pending]); eng.accept(u(1, 100 + i))
+        sync(); ar_tok_s = n_ar_timed / (time.perf_counter() - t0)
+        eng.prefill(ctx_ids)
+        for r in range(W):
+            eng.step(u_draft=u(cfg.k_max, 1000 + r), u_accept=u(cfg.k_max + 1, 2000 + r))
+        cnt = Counters()
+        phase = {"ldlp": 0.0, "draft": 0.0, "verify": 0.0, "accept": 0.0}
+        us = [(u(cfg.k_max, 3000 + r), u(cfg.k_max + 1, 4000 + r)) for r in range(2 * K)]
+        emitted = 0
+        sync(); t0 = time.perf_counter()
+        for r in range(K):
+            k, na, toks = eng.step(u_draft=us[r][0], u_accept=us[r][1])
+            cnt.add(k, na)
+            emitted += na + 1
+        sync(); dt = time.perf_counter() - t0
+        tok_s = emitted / dt
+        ms_per_step = dt / K * 1e3
+        eng.set_profiling(True)
+        eng.set_kernel_timing(True)
+        for r in range(K, 2 * K):
+            eng.step(u_draft=us[r][0], u_accept=us[r][1])
+            for key, v in eng.phase_times().items():
+                phase[key] += v
+        kt_us, kt_n = eng.kernel_timing()
+        eng.set_kernel_timing(False)
+        eng.set_profiling(False)
+    else:
+        # ---- plain autoregressive decoding on the same kernels: formal sequence + AR baseline
+        eng.prefill(ctx_ids)
+        first = eng.pending
+        formal = np.zeros(n_formal, np.int64)
+        n_ar_timed = min(128, n_formal - 8)
+        for i in range(8):
+            eng.verify([eng.pending]); formal[i] = eng.accept()[1]
+        sync(); t0 = time.perf_counter()
+        for i in range(8, 8 + n_ar_timed):
+            eng.verify([eng.pending]); formal[i] = eng.accept()[1]
+        sync(); ar_s = time.perf_counter() - t0
+        for i in range(8 + n_ar_timed, n_formal):
+            eng.verify([eng.pending]); formal[i] = eng.accept()[1]
+        ar_tok_s = n_ar_timed / ar_s
 
-    # ---- the timed region: W warm-up steps then exactly K steps of the whole hot path
-    eng.prefill(ctx_ids)
-    assert eng.pending == first
-    pos = 0
-    _, pos = run_scripted(eng, formal, pos, W, script)
-    cnt = Counters()
-    eng.set_profiling(True)
-    phase = {"ldlp": 0.0, "draft": 0.0, "verify": 0.0, "accept": 0.0}
-    eng.set_profiling(False)
-    sync(); t0 = time.perf_counter()
-    emitted, pos = run_scripted(eng, formal, pos, K, script[W:], counters=cnt)
-    sync(); dt = time.perf_counter() - t0
-    tok_s = emitted / dt
-    ms_per_step = dt / K * 1e3
+        # ---- the timed region: W warm-up steps then exactly K steps of the whole hot path
+        eng.prefill(ctx_ids)
+        assert eng.pending == first
+        pos = 0
+        _, pos = run_scripted(eng, formal, pos, W, script)
+        cnt = Counters()
+        eng.set_profiling(True)
+        phase = {"ldlp": 0.0, "draft": 0.0, "verify": 0.0, "accept": 0.0}
+        eng.set_profiling(False)
+        sync(); t0 = time.perf_counter()
+        emitted, pos = run_scripted(eng, formal, pos, K, script[W:], counters=cnt)
+        sync(); dt = time.perf_counter() - t0
+        tok_s = emitted / dt
+        ms_per_step = dt / K * 1e3
 
-    # ---- same steps again with phase events and per-launch events on the dominant kernel
-    eng.prefill(ctx_ids)
-    pos2 = 0
-    _, pos2 = run_scripted(eng, formal, pos2, W, script)
-    eng.set_profiling(True)
-    eng.set_kernel_timing(True)
-    vocab = cfg.vocab
-    from paper_2412_18910_amd.loop import scripted_override
-    for r in range(K):
-        k, _ = eng.ldlp()
-        ov = scripted_override(formal, pos2, k, int(script[W + r]), vocab)
-        kk, na, toks = eng.step(k_force=k, override_ids=ov)
-        pos2 += na + 1
-        for key, v in eng.phase_times().items():
-            phase[key] += v
-    kt_us, kt_n = eng.kernel_timing()
-    eng.set_kernel_timing(False)
-    eng.set_profiling(False)
+        # ---- same steps again with phase events and per-launch events on the dominant kernel
+        eng.prefill(ctx_ids)
+        pos2 = 0
+        _, pos2 = run_scripted(eng, formal, pos2, W, script)
+        eng.set_profiling(True)
+        eng.set_kernel_timing(True)
+        vocab = cfg.vocab
+        from paper_2412_18910_amd.loop import scripted_override
+        for r in range(K):
+            k, _ = eng.ldlp()
+            ov = scripted_override(formal, pos2, k, int(script[W + r]), vocab)
+            kk, na, toks = eng.step(k_force=k, override_ids=ov)
+            pos2 += na + 1
+            for key, v in eng.phase_times().items():
+                phase[key] += v
+        kt_us, kt_n = eng.kernel_timing()
+        eng.set_kernel_timing(False)
+        eng.set_profiling(False)
     gate_up_bytes = 2 * 2 * cfg.d_ffn * cfg.d_model
     kern_us = kt_us / max(kt_n, 1)
     achieved = gate_up_bytes / (kern_us * 1e-6) / 1e9 if kt_n else 0.0
@@ -185,7 +226,9 @@ def main():
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.preset}-shaped full AdaEAGLE loop (LDLP->draft->verify->accept), bs=1, "
-                               f"context {args.context}, scripted acceptance (truncated geometric, mean 3.5), k_max {cfg.k_max}",
+                               f"context {args.context}, " + (f"temperature {T}, natural acceptance of the random-init draft head"
+                                                              if T > 0 else "scripted acceptance (truncated geometric, mean 3.5)")
+                               + f", k_max {cfg.k_max}",
                    "n_layers": cfg.n_layers, "d_model": cfg.d_model, "d_ffn": cfg.d_ffn, "vocab": cfg.vocab},
         "step_us": round(ms_per_step * 1e3, 1),
         "phase_us": {k: round(v / K, 1) for k, v in phase.items()},
