@@ -132,6 +132,14 @@ int ae_set_state(ae_ctx *ctx, int kv_len, int32_t last_tok, int32_t pending, con
  * and y_out its score. */
 int ae_ldlp(ae_ctx *ctx, int *k_out, float *y_out);
 
+/* Training criterion of the LDLP (Sec. 3.3, the asymmetric L1 loss) as an evaluation
+ * function: mean over the n pairs of lambda*|pred - truth| where pred < truth (a short draft
+ * costs a whole target forward) and |pred - truth| otherwise; pred holds raw predictions
+ * (regression output before rounding, or chosen lengths), truth the optimal lengths (host
+ * arrays).  Computed on the device in float64 with a fixed-shape reduction; *out = 0 for
+ * n = 0.  Training itself is not part of this library. */
+int ae_ldlp_loss(ae_ctx *ctx, const float *pred, const int32_t *truth, int n, double lambda, double *out);
+
 /* Eq. 2: draft catch-up over the newly validated slots, then a chain of k-1 further
  * one-row forwards; emits k tokens (argmax of the shared LM head, lowest id on ties;
  * with temperature > 0 inverse-CDF samples driven by u_draft[i] in [0,1)).
@@ -155,9 +163,10 @@ int ae_verify(ae_ctx *ctx, const int32_t *block_ids, int n_rows);
 int ae_last_draft_len(const ae_ctx *ctx);
 int ae_get_draft_logprob(ae_ctx *ctx, float *out);
 
-/* Acceptance and rollback.  Greedy (temperature 0, u ignored): n_accepted = length of
- * the longest draft prefix equal to the target argmax, bonus = target argmax of the
- * next row.  temperature > 0: u (host) holds n_rows uniforms in [0,1): u[i], i < k,
+/* Acceptance and rollback.  Greedy (Sec. 3.1 footnote, the "validated prefix" of Eq. 1;
+ * temperature 0, u ignored): n_accepted = length of the longest draft prefix equal to the
+ * target argmax, bonus = target argmax of the next row.  temperature > 0 (the speculative
+ * sampling rule of Sec. 2.1): u (host) holds n_rows uniforms in [0,1): u[i], i < k,
  * accepts draft token i+1 iff u[i] < min(1, p/p_hat); the first rejection resamples
  * from norm(max(0, p - p_hat)) over the vocabulary, no rejection samples the bonus
  * from the last row; both draws use u[k] by inverse CDF in token order, in float64.

@@ -21,7 +21,8 @@ _CODES = {AE_EINVAL: "AE_EINVAL", AE_ESTATE: "AE_ESTATE", AE_ENOMEM: "AE_ENOMEM"
 EXPORTS = ("ae_init", "ae_free", "ae_last_error", "ae_prefill", "ae_kv_import", "ae_set_state", "ae_ldlp",
            "ae_draft", "ae_verify", "ae_accept", "ae_step", "ae_kv_len", "ae_pending", "ae_get_logits",
            "ae_get_feature", "ae_get_draft_logits", "ae_get_kv_row", "ae_set_profiling", "ae_get_phase_times",
-           "ae_set_kernel_timing", "ae_get_kernel_timing", "ae_last_draft_len", "ae_get_draft_logprob", "ae_set_prefill_mode", "ae_version")
+           "ae_set_kernel_timing", "ae_get_kernel_timing", "ae_last_draft_len", "ae_get_draft_logprob", "ae_set_prefill_mode", "ae_version",
+           "ae_ldlp_loss")
 
 
 class AeConfig(C.Structure):
@@ -82,6 +83,7 @@ def load_library(path=LIB_PATH):
         "ae_last_error": (C.c_char_p, [P]),
         "ae_prefill": (I, [P, i32p, I]),
         "ae_kv_import": (I, [P, I, f32p, f32p, I]),
+        "ae_ldlp_loss": (I, [P, f32p, i32p, I, C.c_double, f64p]),
         "ae_set_state": (I, [P, I, C.c_int32, C.c_int32, f32p]),
         "ae_ldlp": (I, [P, C.POINTER(I), f32p]),
         "ae_draft": (I, [P, I, i32p, f64p, i32p]),
@@ -195,6 +197,13 @@ class Engine:
         k, y = C.c_int(), C.c_float()
         self._chk(self.lib.ae_ldlp(self.h, C.byref(k), C.byref(y)), "ae_ldlp")
         return k.value, y.value
+
+    def ldlp_loss(self, pred, truth, lam):
+        pred, truth = _f32(pred), _i32(truth)
+        out = C.c_double()
+        self._chk(self.lib.ae_ldlp_loss(self.h, _p(pred, C.c_float), _p(truth, C.c_int32), len(pred), float(lam),
+                                        C.byref(out)), "ae_ldlp_loss")
+        return out.value
 
     def draft(self, k, override_ids=None, u_draft=None, want_ids=True):
         out = np.zeros(self.cfg.k_max + 1, np.int32)

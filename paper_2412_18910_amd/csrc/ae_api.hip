@@ -365,6 +365,33 @@ __global__ void finish_prefill_kernel(DevState *st, int32_t *hist, int n) {
   st->n_acc = 0;
 }
 
+// Asymmetric L1 criterion of the LDLP (Sec. 3.3): per pair lambda*|p - t| where the prediction
+// is short of the optimal length, |p - t| otherwise; float64, one workgroup, fixed-shape tree.
+__global__ __launch_bounds__(256) void ldlp_loss_kernel(const float *pred, const int32_t *truth, int n, double lambda,
+                                                        double *out) {
+  __shared__ double sh[256];
+  double tot = 0.0;
+  for (int i = threadIdx.x; i < n; i += 256) {
+    const double diff = (double)pred[i] - (double)truth[i];
+    tot += diff < 0.0 ? lambda * -diff : diff;
+  }
+  sh[threadIdx.x] = tot;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) sh[threadIdx.x] += sh[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *out = n > 0 ? sh[0] / (double)n : 0.0;
+}
+
+// The matrix-core attention multiplies the V rows of masked keys by an exact zero, so every
+// cache row, live or dead, has to hold finite values.
+bool all_finite(const float *p, size_t n) {
+  for (size_t i = 0; i < n; ++i)
+    if (!(p[i] - p[i] == 0.0f)) return false;
+  return true;
+}
+
 bool ids_ok(const ae_ctx *c, const int32_t *ids, int n) {
   for (int i = 0; i < n; ++i)
     if (ids[i] < 0 || ids[i] >= c->cfg.vocab) return false;
@@ -435,7 +462,7 @@ int ae_init(const ae_config *cfg, const ae_weights *w, void *hip_stream, ae_ctx 
   c->ldlp_w_out = w->ldlp_w_out; c->ldlp_b_out = w->ldlp_b_out;
 
   // bf16: re-tile every streamed matrix into the MFMA operand layout (see kernels_mfma.hip)
-  c->fast = g.dtype == AE_BF16 && !getenv("AE_FORCE_GENERIC");
+  c->fast = g.dtype == AE_BF16;
   if (c->fast) {
     bool ok = tileable(c->lm_head) && tileable(c->draft_fc) && g.head_dim % 32 == 0;
     for (auto &l : c->layers)
@@ -607,6 +634,7 @@ int ae_kv_import(ae_ctx *c, int layer, const float *k, const float *v, int n) {
     return fail(c, AE_EINVAL, "ae_kv_import: argument out of range");
   if (n == 0) return AE_OK;
   const size_t cnt = (size_t)n * g.n_kv_heads * g.head_dim;
+  if (!all_finite(k, cnt) || !all_finite(v, cnt)) return fail(c, AE_EINVAL, "ae_kv_import: non-finite value");
   float *tmp = nullptr;
   HIPCHK(c, hipMalloc((void **)&tmp, 2 * cnt * sizeof(float)));
   hipError_t e = hipMemcpy(tmp, k, cnt * sizeof(float), hipMemcpyHostToDevice);
@@ -813,6 +841,27 @@ int ae_step(ae_ctx *c, ae_step_io *io) {
   for (int i = 0; i < acc; ++i) io->tokens[i] = c->h_block[1 + i];
   io->tokens[acc] = b;
   io->us_total = std::chrono::duration<float, std::micro>(std::chrono::steady_clock::now() - t0).count();
+  return AE_OK;
+}
+
+int ae_ldlp_loss(ae_ctx *c, const float *pred, const int32_t *truth, int n, double lambda, double *out) {
+  if (!c) return AE_EINVAL;
+  if (n < 0 || (n > 0 && (!pred || !truth)) || !out || !(lambda >= 0.0))
+    return fail(c, AE_EINVAL, "ae_ldlp_loss: argument out of range");
+  if (n == 0) { *out = 0.0; return AE_OK; }
+  char *buf = nullptr;
+  const size_t off_t = ((size_t)n * 4 + 15) / 16 * 16, off_o = 2 * off_t;
+  HIPCHK(c, hipMalloc((void **)&buf, off_o + 16));
+  hipError_t e = hipMemcpy(buf, pred, (size_t)n * 4, hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy(buf + off_t, truth, (size_t)n * 4, hipMemcpyHostToDevice);
+  if (e == hipSuccess) {
+    ldlp_loss_kernel<<<1, 256, 0, c->stream>>>((const float *)buf, (const int32_t *)(buf + off_t), n, lambda,
+                                               (double *)(buf + off_o));
+    e = hipStreamSynchronize(c->stream);
+  }
+  if (e == hipSuccess) e = hipMemcpy(out, buf + off_o, sizeof(double), hipMemcpyDeviceToHost);
+  hipFree(buf);
+  if (e != hipSuccess) return fail(c, AE_EHIP, std::string("ae_ldlp_loss: ") + hipGetErrorString(e));
   return AE_OK;
 }
 

@@ -61,17 +61,6 @@ def run_scripted(engine, formal, pos, n_steps, script, k_mode="ldlp", k_fixed=4,
     return emitted, pos
 
 
-def ldlp_loss(pred, truth, lam):
-    """Training criterion of the LDLP (Sec. 3.3) as an evaluation function: mean of
-    |pred - truth| over the pairs, scaled by lam > 1 where the prediction is shorter than the
-    optimal draft length (a short draft costs a whole target forward, a long one only draft
-    steps)."""
-    pred = np.asarray(pred, np.float64)
-    truth = np.asarray(truth, np.float64)
-    gap = truth - pred
-    return float(np.mean(np.where(gap > 0, lam * gap, -gap))) if pred.size else 0.0
-
-
 def generate(engine, max_tokens, eos_id=None, u_stream=None):
     """Algorithm 1 as a generation loop: after a prefill, repeat ae_step (LDLP -> draft ->
     verify -> accept) until max_tokens tokens exist or the terminator eos_id was generated;
