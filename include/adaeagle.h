@@ -120,6 +120,16 @@ int ae_set_prefill_mode(ae_ctx *ctx, int mode, int chunk_rows);
  * converted to the cache dtype) for layer `layer` (n_layers = the draft layer) at
  * slots 0..n-1 ...                                                                    */
 int ae_kv_import(ae_ctx *ctx, int layer, const float *k, const float *v, int n);
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the same import as ae_kv_import, staged
+ * through a fixed array that lives in the library's device image instead of a temporary
+ * allocation.  Calls no hipMalloc / hipFree.  Limit: 2 * n * n_kv_heads * head_dim <=
+ * AE_KV_IMPORT_STATIC_MAX_FLOATS (8 MiB of staging per GPU, held until the process ends),
+ * else AE_EINVAL; import longer caches with ae_kv_import.  All contexts on one GPU share
+ * that array: calls to this function that overlap in time on the same GPU race (calls on
+ * one thread, one after the other, are fine: each returns after its kernel has finished). */
+#define AE_KV_IMPORT_STATIC_MAX_FLOATS (2 * 1024 * 1024)
+int ae_kv_import_static(ae_ctx *ctx, int layer, const float *k, const float *v, int n);
 /* ... and declare the state right after an accept: kv_len cached tokens, the token in
  * the last slot, the pending bonus token and the feature row (host float [d]) of the
  * last slot.  The draft cache is taken to be valid for slots 0..kv_len-2. */

@@ -22,7 +22,7 @@ EXPORTS = ("ae_init", "ae_free", "ae_last_error", "ae_prefill", "ae_kv_import", 
            "ae_draft", "ae_verify", "ae_accept", "ae_step", "ae_kv_len", "ae_pending", "ae_get_logits",
            "ae_get_feature", "ae_get_draft_logits", "ae_get_kv_row", "ae_set_profiling", "ae_get_phase_times",
            "ae_set_kernel_timing", "ae_get_kernel_timing", "ae_last_draft_len", "ae_get_draft_logprob", "ae_set_prefill_mode", "ae_version",
-           "ae_ldlp_loss")
+           "ae_kv_import_static", "ae_ldlp_loss")
 
 
 class AeConfig(C.Structure):
@@ -83,6 +83,7 @@ def load_library(path=LIB_PATH):
         "ae_last_error": (C.c_char_p, [P]),
         "ae_prefill": (I, [P, i32p, I]),
         "ae_kv_import": (I, [P, I, f32p, f32p, I]),
+        "ae_kv_import_static": (I, [P, I, f32p, f32p, I]),
         "ae_ldlp_loss": (I, [P, f32p, i32p, I, C.c_double, f64p]),
         "ae_set_state": (I, [P, I, C.c_int32, C.c_int32, f32p]),
         "ae_ldlp": (I, [P, C.POINTER(I), f32p]),
@@ -188,6 +189,11 @@ class Engine:
     def kv_import(self, layer, k, v):
         k, v = _f32(k), _f32(v)
         self._chk(self.lib.ae_kv_import(self.h, layer, _p(k, C.c_float), _p(v, C.c_float), k.shape[0]), "ae_kv_import")
+
+    def kv_import_static(self, layer, k, v):
+        k, v = _f32(k), _f32(v)
+        self._chk(self.lib.ae_kv_import_static(self.h, layer, _p(k, C.c_float), _p(v, C.c_float), k.shape[0]),
+                  "ae_kv_import_static")
 
     def set_state(self, kv_len, last_tok, pending, feat):
         feat = _f32(feat)

@@ -5,15 +5,40 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "ae_internal.h"
 
 using namespace ae;
 
+// Staging area of ae_kv_import_static: device memory that exists from the moment the library
+// is loaded, so that entry point never allocates.  Every GPU holds its own copy at its own
+// address; host code only ever uses the per-device address looked up in static_stage().
+constexpr size_t kStageFloats = (size_t)AE_KV_IMPORT_STATIC_MAX_FLOATS;
+static __device__ __align__(256) float g_kv_stage[kStageFloats];
+
 namespace {
 
 thread_local std::string g_init_error;
+
+constexpr int kMaxDevices = 64;
+std::mutex g_stage_mu;
+float *g_stage_ptr[kMaxDevices] = {};
+
+// Address of g_kv_stage on device `dev`, which must be the current device.
+hipError_t static_stage(int dev, float **out) {
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_stage_mu);
+  if (!g_stage_ptr[dev]) {
+    void *p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_kv_stage));
+    if (e != hipSuccess) return e;
+    g_stage_ptr[dev] = (float *)p;
+  }
+  *out = g_stage_ptr[dev];
+  return hipSuccess;
+}
 
 int fail(ae_ctx *c, int code, const std::string &msg) {
   if (c) c->err = msg; else g_init_error = msg;
@@ -439,6 +464,10 @@ int ae_init(const ae_config *cfg, const ae_weights *w, void *hip_stream, ae_ctx 
   int rc = AE_OK;
   auto bail = [&](int code) { g_init_error = c->err; ae_free(c); return code; };
   if (hipGetDevice(&c->device) != hipSuccess) { c->err = "hipGetDevice failed (no GPU?)"; return bail(AE_EHIP); }
+  {
+    hipError_t e = static_stage(c->device, &c->kv_stage);
+    if (e != hipSuccess) { c->err = std::string("hipGetSymbolAddress(kv stage): ") + hipGetErrorString(e); return bail(AE_EHIP); }
+  }
 
   const int d = g.d_model, dq = g.n_heads * g.head_dim, dkv = g.n_kv_heads * g.head_dim, f = g.d_ffn, V = g.vocab;
   auto conv_layer = [&](const ae_layer_w &s, LayerW &o) -> bool {
@@ -645,6 +674,28 @@ int ae_kv_import(ae_ctx *c, int layer, const float *k, const float *v, int n) {
   }
   hipFree(tmp);
   if (e != hipSuccess) return fail(c, AE_EHIP, std::string("ae_kv_import: ") + hipGetErrorString(e));
+  return AE_OK;
+}
+
+int ae_kv_import_static(ae_ctx *c, int layer, const float *k, const float *v, int n) {
+  if (!c) return AE_EINVAL;
+  const ae_config &g = c->cfg;
+  if (layer < 0 || layer > g.n_layers || n < 0 || n > g.n_ctx_max || !k || !v)
+    return fail(c, AE_EINVAL, "ae_kv_import_static: argument out of range");
+  if (n == 0) return AE_OK;
+  const size_t cnt = (size_t)n * g.n_kv_heads * g.head_dim;
+  if (2 * cnt > kStageFloats)
+    return fail(c, AE_EINVAL, "ae_kv_import_static: 2 * n * n_kv_heads * head_dim exceeds the " +
+                                  std::to_string(kStageFloats) + "-float staging area (use fewer rows or ae_kv_import)");
+  if (!all_finite(k, cnt) || !all_finite(v, cnt)) return fail(c, AE_EINVAL, "ae_kv_import_static: non-finite value");
+  float *stage = c->kv_stage;   // this device's copy of the staging array
+  // the previous user of the staging area (any ctx on this device) has finished: every call
+  // returns only after its import kernel has completed
+  HIPCHK(c, hipMemcpy(stage, k, cnt * sizeof(float), hipMemcpyHostToDevice));
+  HIPCHK(c, hipMemcpy(stage + cnt, v, cnt * sizeof(float), hipMemcpyHostToDevice));
+  launch_kv_import(kv_layer_ptr(c, layer), c->kv_v_offset, g, stage, stage + cnt, n, c->fast, c->stream);
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipGetLastError());
   return AE_OK;
 }
 

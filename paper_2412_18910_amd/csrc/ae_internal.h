@@ -71,6 +71,7 @@ struct ae_ctx {
   size_t kv_layer_stride = 0;      // bytes between layers
   size_t kv_v_offset = 0;          // bytes from a layer's K to its V
   float2 *rope_tab = nullptr;      // [n_ctx_max][head_dim/2] (cos, sin)
+  float *kv_stage = nullptr;       // this device's address of the library's static staging array
 
   // activations (float, kMaxRows rows each)
   float *x = nullptr, *xn = nullptr, *q = nullptr, *kbuf = nullptr, *vbuf = nullptr, *att = nullptr;

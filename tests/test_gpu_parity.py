@@ -317,6 +317,9 @@ def test_kv_import_rejects_non_finite_values():
     with pytest.raises(AdaEagleError) as e:
         eng.kv_import(0, k, bad)
     assert e.value.code == AE_EINVAL
+    with pytest.raises(AdaEagleError) as e:
+        eng.kv_import_static(0, k, bad)
+    assert e.value.code == AE_EINVAL
     eng.kv_import(0, k, v)
     eng.close()
 
