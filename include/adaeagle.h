@@ -61,7 +61,7 @@ typedef struct {
   int32_t ldlp_hidden;   /* width h of the LDLP hidden layers (<= 1024) */
   int32_t ldlp_n_res;    /* residual h->h blocks between input and output layer */
   float temperature;     /* 0: greedy (Sec. 3.1); > 0: rejection sampling (Sec. 2.1) */
-  int32_t ddd_enabled;   /* AdaEAGLE-DDD exit rule (Sec. 3.4, 4.2); greedy only */
+  int32_t ddd_enabled;   /* AdaEAGLE-DDD exit rule (Sec. 3.4, 4.2) */
   float ddd_threshold;   /* log-probability threshold of that rule (the paper picks -0.6) */
   int32_t ldlp_cls;      /* 0: LDLP regresses a scalar, rounded and clamped (Eq. 3)
                             1: classification over the lengths 0..k_max (the "w/ Cls"
@@ -157,11 +157,30 @@ int ae_ldlp_loss(ae_ctx *ctx, const float *pred, const int32_t *truth, int n, do
  * replaces the i-th emitted token before it is chained.  draft_ids_out (host, nullable,
  * room for k_max ids) receives the tokens.
  * With cfg.ddd_enabled the head exits before token s iff s > k AND the log-probability of
- * the s-1 tokens drafted so far is below cfg.ddd_threshold: at least one token is drafted,
- * the longer of the two lengths is kept, never more than k_max; every decision past k costs
- * one host synchronisation.  ae_last_draft_len() tells how many tokens were drafted. */
+ * the s-1 tokens drafted so far (under softmax(logits / T), T = 1 when greedy) is below
+ * cfg.ddd_threshold: at least one token is drafted (for thresholds <= 0), the longer of the
+ * two lengths is kept, never more than k_max; override_ids and u_draft then hold k_max
+ * entries.  Where the rule is evaluated is chosen with ae_set_ddd_mode.
+ * ae_last_draft_len() tells how many tokens were drafted. */
 int ae_draft(ae_ctx *ctx, int k, const int32_t *override_ids, const double *u_draft,
              int32_t *draft_ids_out);
+
+/* Where the exit rule of cfg.ddd_enabled is evaluated (Sec. 3.2 worries about CPU<->GPU
+ * traffic in the decoding loop; Sec. 3.4 / 4.2 give the rule).
+ *  AE_DDD_HOST: the host reads the running log-probability back before every token past k:
+ *    one stream synchronisation per such decision, no wasted launches.
+ *  AE_DDD_DEVICE (default; measured faster at the 7B shape whether the rule extends drafts
+ *    never, sometimes or always): ae_draft enqueues all k_max tokens; the kernels of every token past k
+ *    check a device-side flag at entry and return at once after the rule has said stop.
+ *    No synchronisation inside ae_draft: a whole ae_step synchronises once, in ae_accept.
+ *    The drafted length then lives on the device until ae_accept: the implicit verify block
+ *    is padded to k_max + 1 rows (rows past the drafted length hold stale tokens whose
+ *    cache rows are dead after the rollback) and u_accept must hold k_max + 1 uniforms.
+ *    ae_draft with draft_ids_out != NULL synchronises anyway and un-pads: ae_last_draft_len()
+ *    is exact after it, else only after ae_accept.
+ * Both modes draft the same tokens. */
+enum { AE_DDD_HOST = 0, AE_DDD_DEVICE = 1 };
+int ae_set_ddd_mode(ae_ctx *ctx, int mode);
 
 /* Eq. 1, forward part: target forward of an n_rows block at slots kv_len.. with causal
  * attention over the cache; row i's logits judge block token i+1.  block_ids (host)

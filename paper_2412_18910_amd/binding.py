@@ -22,7 +22,7 @@ EXPORTS = ("ae_init", "ae_free", "ae_last_error", "ae_prefill", "ae_kv_import", 
            "ae_draft", "ae_verify", "ae_accept", "ae_step", "ae_kv_len", "ae_pending", "ae_get_logits",
            "ae_get_feature", "ae_get_draft_logits", "ae_get_kv_row", "ae_set_profiling", "ae_get_phase_times",
            "ae_set_kernel_timing", "ae_get_kernel_timing", "ae_last_draft_len", "ae_get_draft_logprob", "ae_set_prefill_mode", "ae_version",
-           "ae_kv_import_static", "ae_ldlp_loss")
+           "ae_kv_import_static", "ae_ldlp_loss", "ae_set_ddd_mode")
 
 
 class AeConfig(C.Structure):
@@ -103,6 +103,7 @@ def load_library(path=LIB_PATH):
         "ae_get_phase_times": (I, [P, C.POINTER(AePhaseTimes)]),
         "ae_set_kernel_timing": (I, [P, I]),
         "ae_set_prefill_mode": (I, [P, I, I]),
+        "ae_set_ddd_mode": (I, [P, I]),
         "ae_get_kernel_timing": (I, [P, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
         "ae_version": (C.c_char_p, []),
     }
@@ -276,6 +277,11 @@ class Engine:
 
     def set_prefill_mode(self, mode, chunk_rows=0):
         self._chk(self.lib.ae_set_prefill_mode(self.h, int(mode), int(chunk_rows)), "ae_set_prefill_mode")
+
+    DDD_HOST, DDD_DEVICE = 0, 1
+
+    def set_ddd_mode(self, mode):
+        self._chk(self.lib.ae_set_ddd_mode(self.h, int(mode)), "ae_set_ddd_mode")
 
     def set_kernel_timing(self, on=True):
         self._chk(self.lib.ae_set_kernel_timing(self.h, int(on)), "ae_set_kernel_timing")

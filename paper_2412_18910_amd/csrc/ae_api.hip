@@ -74,7 +74,7 @@ Mat make_mat(const void *p, int N, int K) {
 // generic path: Y[r][n] (+)= X[r][:] . W[n][:] + bias[n]
 void gemm(ae_ctx *c, const Mat &W, const float *X, int ldx, int rows, const float *bias, float *Y, int ldy,
           int accumulate) {
-  launch_gemm_generic(W.rowmajor, c->cfg.dtype, W.N, W.K, X, ldx, rows, bias, Y, ldy, accumulate, c->stream);
+  launch_gemm_generic(W.rowmajor, c->cfg.dtype, W.N, W.K, X, ldx, rows, bias, Y, ldy, accumulate, c->stream, c->gate);
 }
 
 bool tileable(const Mat &m) { return m.N % 16 == 0 && m.K % 256 == 0; }
@@ -121,15 +121,18 @@ void run_layer(ae_ctx *c, int li, float *x, int rows, int pos0, const float *nex
     qkv.seg_N[0] = dq; qkv.seg_N[1] = dkv; qkv.seg_N[2] = dkv;
     qkv.rope_tab = c->rope_tab; qkv.Kc = kv_layer_ptr(c, li); qkv.Vc = (char *)kv_layer_ptr(c, li) + c->kv_v_offset;
     qkv.pos0 = pos0; qkv.n_ctx = kv_capacity(g); qkv.hd = g.head_dim;
+    qkv.gate = c->gate;
     launch_gemm_mfma(qkv, s);
-    launch_attention_mfma(c->q, rows, pos0, g, kv_layer_ptr(c, li), c->kv_v_offset, c->attn_part, c->xp_att, s);
+    launch_attention_mfma(c->q, rows, pos0, g, kv_layer_ptr(c, li), c->kv_v_offset, c->attn_part, c->xp_att, s, c->gate);
     GemmLaunch o;
     o.W = &w.wo; o.Xp = c->xp_att; o.rows = rows; o.epi = EPI_RESID; o.Y[0] = x; o.ldy[0] = d; o.seg_N[0] = d;
     o.Xp_out = c->xp_f; o.gain_out = w.ffn_norm; o.ssq_out = c->ssq_f;
+    o.gate = c->gate;
     launch_gemm_mfma(o, s);
     GemmLaunch gu;
     gu.W = &w.f_gu; gu.Xp = c->xp_f; gu.rows = rows; gu.ssq_in = c->ssq_f; gu.P_in = Pd; gu.eps = g.rms_eps;
     gu.epi = EPI_SWIGLU; gu.Xp_out = c->xp_h; gu.seg_N[0] = 2 * f;
+    gu.gate = c->gate;
     const bool timed = c->ktime && c->kt_used + 2 <= (int)c->kt_ev.size();
     if (timed) hipEventRecord(c->kt_ev[c->kt_used], s);
     launch_gemm_mfma(gu, s);
@@ -137,21 +140,23 @@ void run_layer(ae_ctx *c, int li, float *x, int rows, int pos0, const float *nex
     GemmLaunch dn;
     dn.W = &w.w_down; dn.Xp = c->xp_h; dn.rows = rows; dn.epi = EPI_RESID; dn.Y[0] = x; dn.ldy[0] = d; dn.seg_N[0] = d;
     dn.Xp_out = c->xp_a; dn.gain_out = next_gain; dn.ssq_out = c->ssq_a;
+    dn.gate = c->gate;
     launch_gemm_mfma(dn, s);
     c->Pa = Pd;
     return;
   }
-  launch_rmsnorm(x, w.attn_norm, rows, d, g.rms_eps, c->xn, s);
+  launch_rmsnorm(x, w.attn_norm, rows, d, g.rms_eps, c->xn, s, c->gate);
   gemm(c, w.wq, c->xn, d, rows, nullptr, c->q, dq, 0);
   gemm(c, w.wk, c->xn, d, rows, nullptr, c->kbuf, dkv, 0);
   gemm(c, w.wv, c->xn, d, rows, nullptr, c->vbuf, dkv, 0);
-  launch_rope_append(c->q, c->kbuf, c->vbuf, rows, pos0, g, c->rope_tab, kv_layer_ptr(c, li), c->kv_v_offset, false, s);
-  launch_attention(c->q, rows, pos0, g, kv_layer_ptr(c, li), c->kv_v_offset, c->attn_part, c->att, s);
+  launch_rope_append(c->q, c->kbuf, c->vbuf, rows, pos0, g, c->rope_tab, kv_layer_ptr(c, li), c->kv_v_offset, false, s,
+                     c->gate);
+  launch_attention(c->q, rows, pos0, g, kv_layer_ptr(c, li), c->kv_v_offset, c->attn_part, c->att, s, c->gate);
   gemm(c, w.wo, c->att, dq, rows, nullptr, x, d, 1);
-  launch_rmsnorm(x, w.ffn_norm, rows, d, g.rms_eps, c->xn, s);
-  gemm(c, w.w_gate, c->xn, d, rows, nullptr, c->gate, f, 0);
+  launch_rmsnorm(x, w.ffn_norm, rows, d, g.rms_eps, c->xn, s, c->gate);
+  gemm(c, w.w_gate, c->xn, d, rows, nullptr, c->gate_proj, f, 0);
   gemm(c, w.w_up, c->xn, d, rows, nullptr, c->up, f, 0);
-  launch_silu_mul(c->gate, c->up, rows, f, c->hmid, s);
+  launch_silu_mul(c->gate_proj, c->up, rows, f, c->hmid, s, c->gate);
   gemm(c, w.w_down, c->hmid, f, rows, nullptr, x, d, 1);
 }
 
@@ -193,17 +198,18 @@ void draft_rows(ae_ctx *c, const float *feat, int feat_ld, const int32_t *next_i
   hipStream_t s = c->stream;
   const LayerW &dl = c->layers[g.n_layers];
   if (c->fast) {
-    launch_draft_cat_packed(feat, feat_ld, c->tok_emb, next_ids_dev, rows, g.d_model, c->xp_cat, s);
+    launch_draft_cat_packed(feat, feat_ld, c->tok_emb, next_ids_dev, rows, g.d_model, c->xp_cat, s, c->gate);
     GemmLaunch fc;
     fc.W = &c->draft_fc; fc.Xp = c->xp_cat; fc.rows = rows; fc.epi = EPI_STORE; fc.bias = c->draft_fc_b;
     fc.Y[0] = c->x; fc.ldy[0] = g.d_model; fc.seg_N[0] = g.d_model;
     fc.Xp_out = c->xp_a; fc.gain_out = dl.attn_norm; fc.ssq_out = c->ssq_a;
+    fc.gate = c->gate;
     launch_gemm_mfma(fc, s);
     c->Pa = g.d_model / 16;
     run_layer(c, g.n_layers, c->x, rows, slot0, nullptr);   // leaves packed(raw output) in xp_a
     return;
   }
-  launch_draft_cat(feat, feat_ld, c->tok_emb, g.dtype, next_ids_dev, rows, g.d_model, c->cat, s);
+  launch_draft_cat(feat, feat_ld, c->tok_emb, g.dtype, next_ids_dev, rows, g.d_model, c->cat, s, c->gate);
   gemm(c, c->draft_fc, c->cat, 2 * g.d_model, rows, c->draft_fc_b, c->x, g.d_model, 0);
   run_layer(c, g.n_layers, c->x, rows, slot0, nullptr);
 }
@@ -221,17 +227,18 @@ void draft_lm_head(ae_ctx *c, int row, int i) {
     lm.W = &c->lm_head; lm.Xp = c->xp_a; lm.rows = 1; lm.row0 = row; lm.epi = EPI_STORE;
     lm.Y[0] = dl; lm.ldy[0] = g.vocab; lm.seg_N[0] = g.vocab;
     if (greedy) { lm.amax_val = c->amax_val; lm.amax_idx = c->amax_idx; }
+    lm.gate = c->gate;
     launch_gemm_mfma(lm, s);
     if (greedy) {
-      launch_argmax_finish(c->amax_val, c->amax_idx, g.vocab / 16, 1, c->st, i, s);   // argmax + override
+      launch_argmax_finish(c->amax_val, c->amax_idx, g.vocab / 16, 1, c->st, i, s, c->gate);   // argmax + override
       return;
     }
   } else {
     gemm(c, c->lm_head, c->x + (size_t)row * g.d_model, g.d_model, 1, nullptr, dl, g.vocab, 0);
   }
-  if (greedy) launch_argmax(dl, 1, g.vocab, c->st->argmax, s);
-  else launch_sample_draft(dl, g.vocab, g.temperature, c->st, i, c->prob, s);
-  launch_pick_draft(c->st, i, nullptr, s);
+  if (greedy) launch_argmax(dl, 1, g.vocab, c->st->argmax, s, c->gate);
+  else launch_sample_draft(dl, g.vocab, g.temperature, c->st, i, c->prob, s, c->gate);
+  launch_pick_draft(c->st, i, s, c->gate);
 }
 
 void enqueue_ldlp(ae_ctx *c, int slot, int f_row, bool relative_to_accept) {
@@ -450,8 +457,6 @@ int ae_init(const ae_config *cfg, const ae_weights *w, void *hip_stream, ae_ctx 
     return fail(nullptr, AE_EUNSUPPORTED, "n_heads / n_kv_heads must be <= 4");
   if (g.temperature > 0.f && g.vocab > 1024 * 1024)
     return fail(nullptr, AE_EUNSUPPORTED, "temperature > 0 supports vocabularies of up to 1048576 tokens");
-  if (g.ddd_enabled && g.temperature > 0.f)
-    return fail(nullptr, AE_EUNSUPPORTED, "the DDD exit rule is implemented for greedy decoding only");
   if (g.n_ctx_max > kMaxSplits * kAttnChunk) return fail(nullptr, AE_EUNSUPPORTED, "n_ctx_max too large (<= 16384)");
   if (!w->tok_emb || !w->final_norm || !w->lm_head || !w->layers || !w->draft_fc_w || !w->ldlp_w_in ||
       !w->ldlp_b_in || !w->ldlp_w_out || !w->ldlp_b_out || (g.ldlp_n_res > 0 && (!w->ldlp_w_res || !w->ldlp_b_res)))
@@ -557,7 +562,7 @@ int ae_init(const ae_config *cfg, const ae_weights *w, void *hip_stream, ae_ctx 
       (rc = dev_alloc(c, &c->x, R * d)) || (rc = dev_alloc(c, &c->xn, R * d)) ||
       (rc = dev_alloc(c, &c->q, R * dq)) || (rc = dev_alloc(c, &c->kbuf, R * dkv)) ||
       (rc = dev_alloc(c, &c->vbuf, R * dkv)) || (rc = dev_alloc(c, &c->att, R * dmax)) ||
-      (rc = dev_alloc(c, &c->gate, R * f)) || (rc = dev_alloc(c, &c->up, R * f)) ||
+      (rc = dev_alloc(c, &c->gate_proj, R * f)) || (rc = dev_alloc(c, &c->up, R * f)) ||
       (rc = dev_alloc(c, &c->hmid, R * f)) || (rc = dev_alloc(c, &c->F, R * d)) ||
       (rc = dev_alloc(c, &c->cat, R * 2 * d)) || (rc = dev_alloc(c, &c->logits, (size_t)(g.k_max + 1) * V)) ||
       (rc = dev_alloc(c, &c->dlogits, (size_t)(g.k_max > 0 ? g.k_max : 1) * V)) ||
@@ -742,36 +747,51 @@ int ae_draft(ae_ctx *c, int k, const int32_t *override_ids, const double *u_draf
   if (override_ids)
     for (int i = 0; i < n_ov; ++i)
       if (override_ids[i] >= g.vocab) return fail(c, AE_EINVAL, "ae_draft: override id out of range");
-  if (g.temperature > 0.f && k > 0 && !u_draft) return fail(c, AE_EINVAL, "ae_draft: temperature > 0 needs u_draft");
+  const bool sampling = g.temperature > 0.f;
+  if (sampling && n_ov > 0 && !u_draft) return fail(c, AE_EINVAL, "ae_draft: temperature > 0 needs u_draft");
+  if (sampling)
+    for (int i = 0; i < n_ov; ++i)
+      if (!(u_draft[i] >= 0.0 && u_draft[i] < 1.0)) return fail(c, AE_EINVAL, "ae_draft: u_draft outside [0,1)");
   hipStream_t s = c->stream;
-  // upload the override table (-1 = keep the head's own token) and the sampling uniforms
+  // upload the override table (-1 = keep the head's own token), the chain gate and the sampling uniforms
   DevState *up = (DevState *)c->h_ids;
   for (int i = 0; i < kMaxRows; ++i) up->override_ids[i] = (override_ids && i < n_ov) ? override_ids[i] : -1;
-  HIPCHK(c, hipMemcpyAsync(c->st->override_ids, up->override_ids, sizeof(up->override_ids), hipMemcpyHostToDevice, s));
-  if (g.temperature > 0.f && k > 0) {
-    for (int i = 0; i < k; ++i) {
-      if (!(u_draft[i] >= 0.0 && u_draft[i] < 1.0)) return fail(c, AE_EINVAL, "ae_draft: u_draft outside [0,1)");
-      up->u_draft[i] = u_draft[i];
-    }
-    HIPCHK(c, hipMemcpyAsync(c->st->u_draft, up->u_draft, sizeof(double) * k, hipMemcpyHostToDevice, s));
+  up->draft_live = 1;
+  up->draft_len = 0;
+  HIPCHK(c, hipMemcpyAsync(c->st->override_ids, up->override_ids, sizeof(up->override_ids) + 2 * sizeof(int32_t),
+                           hipMemcpyHostToDevice, s));
+  if (sampling && n_ov > 0) {
+    for (int i = 0; i < n_ov; ++i) up->u_draft[i] = u_draft[i];
+    HIPCHK(c, hipMemcpyAsync(c->st->u_draft, up->u_draft, sizeof(double) * n_ov, hipMemcpyHostToDevice, s));
   }
   // catch-up over the slots validated by the last accept: true feature + following token
   draft_rows(c, c->F + (size_t)(c->nF - catch_rows) * g.d_model, g.d_model, c->hist + c->dlen + 1, catch_rows, c->dlen);
   c->dlen = n;
   const float *fh = c->x + (size_t)(catch_rows - 1) * g.d_model;
   int fh_row = catch_rows - 1;
+  // AdaEAGLE-DDD (Sec. 3.4, 4.2): past the predicted length the head exits unless the
+  // log-probability of the tokens drafted so far is still at least the threshold.  Host mode
+  // reads the running sum back before every such token; device mode enqueues all k_max tokens
+  // and lets the kernels of the tokens past k return at entry once the device-side rule says
+  // stop (the verify block is then padded to k_max + 1 rows and ae_accept takes the drafted
+  // length from the device).
+  const bool dev_rule = g.ddd_enabled && c->ddd_mode == AE_DDD_DEVICE;
+  bool gated = false;
   int i = 0;
-  float cum = 0.f;   // log-probability of the tokens drafted so far (host copy, DDD only)
   for (; i < g.k_max; ++i) {
     if (i >= k) {
-      // past the predicted length: exit unless the DDD rule says the sequence is still likely
       if (!g.ddd_enabled) break;
-      if (i > 0) {
+      if (i == 0) {
+        if (!(0.f >= g.ddd_threshold)) break;   // the empty sequence has log-probability 0
+      } else if (dev_rule) {
+        c->gate = &c->st->draft_live;
+        gated = true;
+      } else {
+        c->gate = nullptr;
         int rc = read_state(c);
         if (rc) return rc;
-        cum = c->h_st->cum_logp;
+        if (!(c->h_st->cum_logp >= g.ddd_threshold)) break;
       }
-      if (!(cum >= g.ddd_threshold)) break;
     }
     if (i > 0) {  // chain: the head's previous output replaces the feature
       draft_rows(c, fh, g.d_model, c->st->draft_ids + (i - 1), 1, n - 1 + i);
@@ -779,16 +799,24 @@ int ae_draft(ae_ctx *c, int k, const int32_t *override_ids, const double *u_draf
       fh_row = 0;
     }
     draft_lm_head(c, fh_row, i);
-    if (g.ddd_enabled) launch_draft_logprob(c->dlogits + (size_t)i * g.vocab, g.vocab, c->st, i, s);
+    if (g.ddd_enabled)
+      launch_draft_logprob(c->dlogits + (size_t)i * g.vocab, g.vocab, g.temperature, c->st, i, k, g.ddd_threshold, s, c->gate);
   }
-  k = i;
+  c->gate = nullptr;
+  k = i;   // tokens enqueued; with a gated tail the number drafted is st->draft_len <= k
   c->cur_k = k;
   c->cur_k_last = k;
+  c->k_on_device = gated;
   c->have_draft = true;
   c->have_verify = false;
   if (out && k > 0) {
     int rc = read_state(c);
     if (rc) return rc;
+    if (gated) {   // the caller synchronised anyway: from here on the host knows the length
+      k = c->h_st->draft_len;
+      c->cur_k = c->cur_k_last = k;
+      c->k_on_device = false;
+    }
     memcpy(out, c->h_st->draft_ids, sizeof(int32_t) * k);
   }
   return AE_OK;
@@ -832,9 +860,10 @@ int ae_accept(ae_ctx *c, const double *u, int *n_accepted, int32_t *bonus) {
       up->u_accept[i] = u[i];
     }
     HIPCHK(c, hipMemcpyAsync(c->st->u_accept, up->u_accept, sizeof(double) * rows, hipMemcpyHostToDevice, c->stream));
-    launch_accept_sample(c->logits, c->dlogits, g.vocab, rows - 1, g.temperature, c->st, c->hist, n, c->prob, c->stream);
+    launch_accept_sample(c->logits, c->dlogits, g.vocab, rows - 1, c->k_on_device, g.temperature, c->st, c->hist, n,
+                         c->prob, c->stream);
   } else {
-    launch_accept_greedy(c->st, c->hist, n, rows, c->stream);
+    launch_accept_greedy(c->st, c->hist, n, rows, c->k_on_device, c->stream);
   }
   // Alg. 1 predicts the next draft length right after the verification
   const bool spec = c->have_draft;
@@ -848,6 +877,8 @@ int ae_accept(ae_ctx *c, const double *u, int *n_accepted, int32_t *bonus) {
   c->h_hist[c->kv_len] = c->pending;
   memcpy(c->h_block.data(), c->h_st->block, sizeof(int32_t) * kMaxRows);
   c->nF = acc + 1;
+  if (c->k_on_device) c->cur_k_last = c->h_st->draft_len;   // padded block: the drafted length arrives here
+  c->k_on_device = false;
   c->have_verify = c->have_draft = false;
   c->cur_k = 0;
   c->k_next_valid = spec;
@@ -872,7 +903,7 @@ int ae_step(ae_ctx *c, ae_step_io *io) {
   }
   if (prof) hipEventRecord(c->ev[1], s);
   if ((rc = ae_draft(c, k, io->override_ids, io->u_draft, nullptr))) return rc;
-  k = c->cur_k;   // the DDD rule may have extended the draft
+  k = c->cur_k;   // the DDD rule may have extended the draft (device rule: padded to k_max)
   if (prof) hipEventRecord(c->ev[2], s);
   if ((rc = ae_verify(c, nullptr, k + 1))) return rc;
   if (prof) hipEventRecord(c->ev[3], s);
@@ -886,7 +917,7 @@ int ae_step(ae_ctx *c, ae_step_io *io) {
     for (int i = 0; i < 4; ++i) hipEventElapsedTime(&ms[i], c->ev[i], c->ev[i + 1]);
     c->last_times = {ms[0] * 1e3f, ms[1] * 1e3f, ms[2] * 1e3f, ms[3] * 1e3f};
   }
-  io->k = k;
+  io->k = c->cur_k_last;
   io->n_accepted = acc;
   io->n_tokens = acc + 1;
   for (int i = 0; i < acc; ++i) io->tokens[i] = c->h_block[1 + i];
@@ -913,6 +944,14 @@ int ae_ldlp_loss(ae_ctx *c, const float *pred, const int32_t *truth, int n, doub
   if (e == hipSuccess) e = hipMemcpy(out, buf + off_o, sizeof(double), hipMemcpyDeviceToHost);
   hipFree(buf);
   if (e != hipSuccess) return fail(c, AE_EHIP, std::string("ae_ldlp_loss: ") + hipGetErrorString(e));
+  return AE_OK;
+}
+
+int ae_set_ddd_mode(ae_ctx *c, int mode) {
+  if (!c) return AE_EINVAL;
+  if (mode != AE_DDD_HOST && mode != AE_DDD_DEVICE) return fail(c, AE_EINVAL, "ae_set_ddd_mode: unknown mode");
+  if (c->have_draft) return fail(c, AE_ESTATE, "ae_set_ddd_mode: a draft is pending (accept first)");
+  c->ddd_mode = mode;
   return AE_OK;
 }
 

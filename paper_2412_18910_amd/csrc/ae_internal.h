@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 #include <string>
@@ -26,6 +27,11 @@ struct DevState {
   float y_next;             // LDLP scalar before rounding
   int32_t draft_ids[kMaxRows];
   int32_t override_ids[kMaxRows];
+  // Device-gated DDD chain (uploaded together with override_ids): every kernel of a draft token
+  // past the predicted length reads draft_live at entry and returns when it is 0; draft_len
+  // counts the tokens drafted.
+  int32_t draft_live;
+  int32_t draft_len;
   int32_t block[kMaxRows];  // ids of the verify block
   int32_t argmax[kMaxRows]; // per-row argmax of the last LM-head call
   double u_draft[kMaxRows];
@@ -33,6 +39,15 @@ struct DevState {
   float cum_logp;           // log-probability of the current draft sequence (DDD exit rule)
   float draft_lp[kMaxRows]; // per-token log-probabilities
 };
+static_assert(offsetof(DevState, draft_len) == offsetof(DevState, override_ids) + sizeof(int32_t) * (kMaxRows + 1),
+              "override_ids, draft_live, draft_len are uploaded as one range");
+static_assert(offsetof(DevState, u_draft) % 8 == 0, "doubles must stay aligned");
+
+// A kernel launched with a non-null gate pointer does nothing when *gate == 0.
+#define AE_GATE(gate)                          \
+  do {                                         \
+    if ((gate) != nullptr && *(gate) == 0) return; \
+  } while (0)
 
 // Weight matrix handle: row-major source plus (bf16 fast path) the re-tiled copy.
 struct Mat {
@@ -75,7 +90,7 @@ struct ae_ctx {
 
   // activations (float, kMaxRows rows each)
   float *x = nullptr, *xn = nullptr, *q = nullptr, *kbuf = nullptr, *vbuf = nullptr, *att = nullptr;
-  float *gate = nullptr, *up = nullptr, *hmid = nullptr;
+  float *gate_proj = nullptr, *up = nullptr, *hmid = nullptr;
   float *F = nullptr;              // feature rows (post final norm)
   float *fhat = nullptr;           // draft-head output rows
   float *cat = nullptr;            // [rows][2d] draft fc input
@@ -106,6 +121,9 @@ struct ae_ctx {
   // host-side state machine
   int kv_len = 0, dlen = 0, nF = 0;
   int cur_k = 0, cur_k_last = 0, block_rows = 0;
+  int ddd_mode = AE_DDD_DEVICE;    // AE_DDD_HOST / AE_DDD_DEVICE
+  bool k_on_device = false;        // the last draft's length is only known on the device (st->draft_len)
+  const int32_t *gate = nullptr;   // gate of the kernels being enqueued (device-gated DDD chain), else nullptr
   int32_t pending = 0;
   bool have_pending = false, have_draft = false, have_verify = false, k_next_valid = false;
   int k_next = 0;
@@ -130,19 +148,26 @@ namespace ae {
 
 // ---- generic kernels (kernels_generic.hip); all launches are asynchronous on `s` ----
 void launch_embed(const void *emb, int dtype, const int32_t *ids_dev, int rows, int d, float *out, hipStream_t s);
-void launch_rmsnorm(const float *x, const float *g, int rows, int d, float eps, float *out, hipStream_t s);
+void launch_rmsnorm(const float *x, const float *g, int rows, int d, float eps, float *out, hipStream_t s,
+                    const int32_t *gate = nullptr);
 // Y[r][n] (+)= sum_k X[r][k] W[n][k] + bias[n];  accumulate != 0 adds into Y (residual)
 void launch_gemm_generic(const void *W, int dtype, int N, int K, const float *X, int ldx, int rows,
-                         const float *bias, float *Y, int ldy, int accumulate, hipStream_t s);
-void launch_silu_mul(const float *gate, const float *up, int rows, int f, float *out, hipStream_t s);
-void launch_argmax(const float *logits, int rows, int V, int32_t *out_ids, hipStream_t s);
+                         const float *bias, float *Y, int ldy, int accumulate, hipStream_t s,
+                         const int32_t *gate = nullptr);
+void launch_silu_mul(const float *gate_proj, const float *up, int rows, int f, float *out, hipStream_t s,
+                     const int32_t *gate = nullptr);
+void launch_argmax(const float *logits, int rows, int V, int32_t *out_ids, hipStream_t s, const int32_t *gate = nullptr);
 void launch_draft_cat(const float *feat, int feat_ld, const void *emb, int dtype, const int32_t *next_ids,
-                      int rows, int d, float *cat, hipStream_t s);
-void launch_pick_draft(DevState *st, int i, int32_t *hist_slot, hipStream_t s);
-// log softmax(logits)[draft token i] -> st->draft_lp[i], added to st->cum_logp (reset when i == 0)
-void launch_draft_logprob(const float *logits, int V, DevState *st, int i, hipStream_t s);
+                      int rows, int d, float *cat, hipStream_t s, const int32_t *gate = nullptr);
+void launch_pick_draft(DevState *st, int i, hipStream_t s, const int32_t *gate = nullptr);
+// DDD bookkeeping behind draft token i: log softmax(logits / T)[token i] -> st->draft_lp[i], added
+// to st->cum_logp (reset when i == 0); st->draft_len = i + 1; and the exit rule for the NEXT
+// token: st->draft_live = 0 when i + 1 >= k and the sequence log-probability is below theta.
+void launch_draft_logprob(const float *logits, int V, float T, DevState *st, int i, int k, float theta, hipStream_t s,
+                          const int32_t *gate = nullptr);
 void launch_build_block(DevState *st, const int32_t *hist, int kv_len, int k, hipStream_t s);
-void launch_accept_greedy(DevState *st, int32_t *hist, int kv_len, int rows, hipStream_t s);
+// k_on_device: the draft length is st->draft_len (the block is padded to `rows` rows)
+void launch_accept_greedy(DevState *st, int32_t *hist, int kv_len, int rows, bool k_on_device, hipStream_t s);
 void launch_ldlp_gather(const void *emb, int dtype, const int32_t *hist, const float *F, int d, int in_mode,
                         int kv_len_minus1_or_neg, int f_row, const DevState *st, float *u, hipStream_t s);
 void launch_ldlp_tail(const float *z0, const void *w_res, int dtype, const float *b_res, const float *w_out,
@@ -155,13 +180,14 @@ size_t kv_layer_bytes(const ae_config &c);
 size_t kv_v_offset_bytes(const ae_config &c);
 int kv_capacity(const ae_config &c);   // n_ctx_max rounded up to a whole attention chunk
 void launch_rope_append(float *q, const float *k, const float *v, int rows, int pos0, const ae_config &c,
-                        const float2 *rope_tab, void *kv_layer, size_t v_off, bool tiled, hipStream_t s);
+                        const float2 *rope_tab, void *kv_layer, size_t v_off, bool tiled, hipStream_t s,
+                        const int32_t *gate = nullptr);
 void launch_attn_merge(const float *part, int rows, const ae_config &c, int n_chunks, float *out, hipStream_t s);
 // bf16 MFMA attention over the tiled cache layout (kernels_attn_mfma.hip)
 void launch_attention_mfma(const float *q, int rows, int pos0, const ae_config &c, const void *kv_layer, size_t v_off,
-                           float *part, void *Xp_out, hipStream_t s);
+                           float *part, void *Xp_out, hipStream_t s, const int32_t *gate = nullptr);
 void launch_attention(const float *q, int rows, int pos0, const ae_config &c, const void *kv_layer, size_t v_off,
-                      float *part, float *out, hipStream_t s);
+                      float *part, float *out, hipStream_t s, const int32_t *gate = nullptr);
 void launch_kv_import(void *kv_layer, size_t v_off, const ae_config &c, const float *k_dev, const float *v_dev, int n,
                       bool tiled, hipStream_t s);
 void launch_kv_export(const void *kv_layer, size_t v_off, const ae_config &c, int which, int slot, float *out_dev,
@@ -170,9 +196,12 @@ size_t attn_part_floats(const ae_config &c);
 
 // ---- T > 0 sampling (kernels_sample.hip) ----
 size_t sample_scratch_doubles(int V);   // size of the scratch both launches below take
-void launch_sample_draft(const float *logits, int V, float T, DevState *st, int i, double *scratch, hipStream_t s);
-void launch_accept_sample(const float *tl, const float *dl, int V, int k, float T, DevState *st, int32_t *hist,
-                          int kv_len, double *prob, hipStream_t s);
+void launch_sample_draft(const float *logits, int V, float T, DevState *st, int i, double *scratch, hipStream_t s,
+                         const int32_t *gate = nullptr);
+// k = draft tokens the block holds room for (rows - 1); k_on_device: only the first
+// st->draft_len of them were drafted (padded block of the device-gated DDD chain)
+void launch_accept_sample(const float *tl, const float *dl, int V, int k, bool k_on_device, float T, DevState *st,
+                          int32_t *hist, int kv_len, double *prob, hipStream_t s);
 
 // ---- bf16 MFMA path (kernels_mfma.hip) ----
 // Row-block nb of a row-major [N,K] matrix -> row-block nb_off + nb*nb_stride of a fused
@@ -202,14 +231,16 @@ struct GemmLaunch {
   const float2 *rope_tab = nullptr;
   void *Kc = nullptr, *Vc = nullptr;
   int pos0 = 0, n_ctx = 0, hd = 0;
+  const int32_t *gate = nullptr;  // see AE_GATE
 };
 void launch_gemm_mfma(const GemmLaunch &L, hipStream_t s);
-void launch_argmax_finish(const float *val, const int32_t *idx, int NB, int rows, DevState *st, int pick_i, hipStream_t s);
+void launch_argmax_finish(const float *val, const int32_t *idx, int NB, int rows, DevState *st, int pick_i, hipStream_t s,
+                          const int32_t *gate = nullptr);
 void launch_embed_packed(const void *emb, const int32_t *ids_dev, int rows, int d, const float *gain, float *x,
                          void *Xp, float *ssq, hipStream_t s);
 void launch_pack_rows(const float *src, int ld, int rows, int K, const float *gain, void *Xp, hipStream_t s);
 void launch_draft_cat_packed(const float *feat, int feat_ld, const void *emb, const int32_t *next_ids, int rows, int d,
-                             void *Xp, hipStream_t s);
+                             void *Xp, hipStream_t s, const int32_t *gate = nullptr);
 
 // ---- dense prompt pass (kernels_dense.hip); packed buffers hold RB row-blocks ----
 // Same GemmLaunch as the decode GEMM (rows = rows of the chunk, row0 unused); rinv != nullptr

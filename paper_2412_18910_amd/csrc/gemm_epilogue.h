@@ -36,6 +36,7 @@ struct GemmArgs {
   const float2 *rope_tab;   // [slot][hd/2] (cos, sin)
   uint16_t *Kc, *Vc;        // this layer's tiled bf16 cache (layouts of kernels_attn_mfma.hip)
   int pos0, n_ctx, hd;
+  const int32_t *gate;      // nullable: the kernel does nothing when *gate == 0
 };
 
 __device__ __forceinline__ uint16_t f2bf_rne(float f) {

@@ -58,7 +58,8 @@ __device__ __forceinline__ size_t v_index(int kh, int d, int slot, int hd, int n
 // grid (rows, H + 2*Hkv), block hd/2.  Rotate-half pairing (i, i + hd/2).
 template <typename T>
 __global__ void rope_append_kernel(float *q, const float *k, const float *v, int pos0, int H, int Hkv, int hd,
-                                   int n_ctx, bool tiled, const float2 *tab, T *Kc, T *Vc) {
+                                   int n_ctx, bool tiled, const float2 *tab, T *Kc, T *Vc, const int32_t *gate) {
+  AE_GATE(gate);
   const int r = blockIdx.x, hs = blockIdx.y, i = threadIdx.x, half = hd / 2;
   const int slot = pos0 + r;
   const float2 cs = tab[(size_t)slot * half + i];
@@ -82,15 +83,16 @@ __global__ void rope_append_kernel(float *q, const float *k, const float *v, int
 }
 
 void launch_rope_append(float *q, const float *k, const float *v, int rows, int pos0, const ae_config &c,
-                        const float2 *rope_tab, void *kv_layer, size_t v_off, bool tiled, hipStream_t s) {
+                        const float2 *rope_tab, void *kv_layer, size_t v_off, bool tiled, hipStream_t s,
+                        const int32_t *gate) {
   const dim3 grid(rows, c.n_heads + 2 * c.n_kv_heads);
   void *vc = (char *)kv_layer + v_off;
   if (c.dtype == AE_BF16)
     rope_append_kernel<bf16_t><<<grid, c.head_dim / 2, 0, s>>>(q, k, v, pos0, c.n_heads, c.n_kv_heads, c.head_dim,
-                                                               kv_capacity(c), tiled, rope_tab, (bf16_t *)kv_layer, (bf16_t *)vc);
+                                                               kv_capacity(c), tiled, rope_tab, (bf16_t *)kv_layer, (bf16_t *)vc, gate);
   else
     rope_append_kernel<float><<<grid, c.head_dim / 2, 0, s>>>(q, k, v, pos0, c.n_heads, c.n_kv_heads, c.head_dim,
-                                                              kv_capacity(c), tiled, rope_tab, (float *)kv_layer, (float *)vc);
+                                                              kv_capacity(c), tiled, rope_tab, (float *)kv_layer, (float *)vc, gate);
 }
 
 // ------------------------------------------------------------------ attention, split-KV partials
@@ -122,8 +124,9 @@ template <> struct Vec8<float> {
 template <typename T, int HD>
 __global__ __launch_bounds__(256) void attn_partial_kernel(const float *q, int rows, int pos0, int H, int Hkv,
                                                            int n_ctx, const T *Kc, const T *Vc, float *part,
-                                                           float scale) {
+                                                           float scale, const int32_t *gate) {
   extern __shared__ float smem[];
+  AE_GATE(gate);
   const int kh = blockIdx.x, chunk = blockIdx.y, n_chunks = gridDim.y;
   const int G = H / Hkv, R = rows * G;
   const int c0 = chunk * kAttnChunk;
@@ -235,7 +238,9 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(const float *q, int r
 
 // merge of the chunk partials, grid (rows*H), block HD; fixed chunk order
 template <int HD>
-__global__ void attn_merge_kernel(const float *part, int rows, int H, int Hkv, int n_chunks, float *out) {
+__global__ void attn_merge_kernel(const float *part, int rows, int H, int Hkv, int n_chunks, float *out,
+                                  const int32_t *gate) {
+  AE_GATE(gate);
   const int m = blockIdx.x / H, h = blockIdx.x % H, d = threadIdx.x;
   const int G = H / Hkv, kh = h / G, r = m * G + (h % G), R = rows * G;
   float mx = -INFINITY;
@@ -261,13 +266,13 @@ size_t attn_part_floats(const ae_config &c) {
 
 void launch_attn_merge(const float *part, int rows, const ae_config &c, int n_chunks, float *out, hipStream_t s) {
   if (c.head_dim == 128)
-    attn_merge_kernel<128><<<rows * c.n_heads, 128, 0, s>>>(part, rows, c.n_heads, c.n_kv_heads, n_chunks, out);
+    attn_merge_kernel<128><<<rows * c.n_heads, 128, 0, s>>>(part, rows, c.n_heads, c.n_kv_heads, n_chunks, out, nullptr);
   else
-    attn_merge_kernel<64><<<rows * c.n_heads, 64, 0, s>>>(part, rows, c.n_heads, c.n_kv_heads, n_chunks, out);
+    attn_merge_kernel<64><<<rows * c.n_heads, 64, 0, s>>>(part, rows, c.n_heads, c.n_kv_heads, n_chunks, out, nullptr);
 }
 
 void launch_attention(const float *q, int rows, int pos0, const ae_config &c, const void *kv_layer, size_t v_off,
-                      float *part, float *out, hipStream_t s) {
+                      float *part, float *out, hipStream_t s, const int32_t *gate) {
   const int n_chunks = (pos0 + rows + kAttnChunk - 1) / kAttnChunk;
   const int G = c.n_heads / c.n_kv_heads, R = rows * G;
   const size_t sm = ((size_t)R * c.head_dim + (size_t)R * kAttnChunk + 2 * R) * sizeof(float);
@@ -279,8 +284,8 @@ void launch_attention(const float *q, int rows, int pos0, const ae_config &c, co
     (void)hipFuncSetAttribute((const void *)attn_partial_kernel<T, HD>, hipFuncAttributeMaxDynamicSharedMemorySize, \
                               (int)sm);                                                                        \
   attn_partial_kernel<T, HD><<<grid, 256, sm, s>>>(q, rows, pos0, c.n_heads, c.n_kv_heads, kv_capacity(c),      \
-                                                   (const T *)kv_layer, (const T *)vc, part, scale);            \
-  attn_merge_kernel<HD><<<rows * c.n_heads, HD, 0, s>>>(part, rows, c.n_heads, c.n_kv_heads, n_chunks, out);
+                                                   (const T *)kv_layer, (const T *)vc, part, scale, gate);      \
+  attn_merge_kernel<HD><<<rows * c.n_heads, HD, 0, s>>>(part, rows, c.n_heads, c.n_kv_heads, n_chunks, out, gate);
   if (c.dtype == AE_BF16) {
     if (c.head_dim == 128) { AE_ATTN(bf16_t, 128) } else { AE_ATTN(bf16_t, 64) }
   } else {

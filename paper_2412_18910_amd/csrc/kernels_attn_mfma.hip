@@ -27,9 +27,10 @@ namespace ae {
 template <int HD>
 __global__ __launch_bounds__(256) void attn_mfma_kernel(const float *q, int rows, int pos0, int H, int Hkv, int n_ctx,
                                                         const u32x4 *Kc, const u32x4 *Vc, float *part,
-                                                        float scale_log2e) {
+                                                        float scale_log2e, const int32_t *gate) {
   constexpr int DT = HD / 32, VT = HD / 16;
   extern __shared__ u32x4 smem[];
+  AE_GATE(gate);
   const int kh = blockIdx.x, chunk = blockIdx.y, n_chunks = gridDim.y;
   const int G = H / Hkv, R = rows * G, MT = (R + 15) / 16;
   u32x4 *Qs = smem;                                           // [MT][DT][2][64]
@@ -178,11 +179,12 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const float *q, int rows
 // input of the output projection (k index = h*HD + d).
 template <int HD>
 __global__ __launch_bounds__(256) void attn_merge_log2_kernel(const float *part, int rows, int H, int Hkv, int n_chunks,
-                                                              u32x4 *Xp_out) {
+                                                              u32x4 *Xp_out, const int32_t *gate) {
   constexpr int DQ = HD / 4, CL = 256 / DQ;
   __shared__ float ms[kMaxSplits];
   __shared__ float4 nums[CL][DQ];
   __shared__ float dens[CL];
+  AE_GATE(gate);
   const int mrow = blockIdx.x / H, h = blockIdx.x % H, dq = threadIdx.x % DQ, cl = threadIdx.x / DQ;
   const int G = H / Hkv, kh = h / G, r = mrow * G + (h % G), R = rows * G;
   const float *base = part + ((size_t)kh * n_chunks * R + r) * (HD + 2);
@@ -221,7 +223,7 @@ __global__ __launch_bounds__(256) void attn_merge_log2_kernel(const float *part,
 }
 
 void launch_attention_mfma(const float *q, int rows, int pos0, const ae_config &c, const void *kv_layer, size_t v_off,
-                           float *part, void *Xp_out, hipStream_t s) {
+                           float *part, void *Xp_out, hipStream_t s, const int32_t *gate) {
   const int n_chunks = (pos0 + rows + kAttnChunk - 1) / kAttnChunk;
   const int G = c.n_heads / c.n_kv_heads, R = rows * G, MT = (R + 15) / 16;
   const int HD = c.head_dim;
@@ -233,13 +235,13 @@ void launch_attention_mfma(const float *q, int rows, int pos0, const ae_config &
   if (HD == 128) {
     if (sm > 48 * 1024)
       (void)hipFuncSetAttribute((const void *)attn_mfma_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
-    attn_mfma_kernel<128><<<grid, 256, sm, s>>>(q, rows, pos0, c.n_heads, c.n_kv_heads, cap, Kc, Vc, part, scale_log2e);
-    attn_merge_log2_kernel<128><<<rows * c.n_heads, 256, 0, s>>>(part, rows, c.n_heads, c.n_kv_heads, n_chunks, (u32x4 *)Xp_out);
+    attn_mfma_kernel<128><<<grid, 256, sm, s>>>(q, rows, pos0, c.n_heads, c.n_kv_heads, cap, Kc, Vc, part, scale_log2e, gate);
+    attn_merge_log2_kernel<128><<<rows * c.n_heads, 256, 0, s>>>(part, rows, c.n_heads, c.n_kv_heads, n_chunks, (u32x4 *)Xp_out, gate);
   } else {
     if (sm > 48 * 1024)
       (void)hipFuncSetAttribute((const void *)attn_mfma_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
-    attn_mfma_kernel<64><<<grid, 256, sm, s>>>(q, rows, pos0, c.n_heads, c.n_kv_heads, cap, Kc, Vc, part, scale_log2e);
-    attn_merge_log2_kernel<64><<<rows * c.n_heads, 256, 0, s>>>(part, rows, c.n_heads, c.n_kv_heads, n_chunks, (u32x4 *)Xp_out);
+    attn_mfma_kernel<64><<<grid, 256, sm, s>>>(q, rows, pos0, c.n_heads, c.n_kv_heads, cap, Kc, Vc, part, scale_log2e, gate);
+    attn_merge_log2_kernel<64><<<rows * c.n_heads, 256, 0, s>>>(part, rows, c.n_heads, c.n_kv_heads, n_chunks, (u32x4 *)Xp_out, gate);
   }
 }
 

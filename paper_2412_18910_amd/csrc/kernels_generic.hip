@@ -54,8 +54,10 @@ void launch_embed(const void *emb, int dtype, const int32_t *ids_dev, int rows, 
 
 // ------------------------------------------------------------------ RMSNorm
 // out = (x / sqrt(mean(x^2) + eps)) * g, one workgroup per row
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const float *x, const float *g, int d, float eps, float *out) {
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float *x, const float *g, int d, float eps, float *out,
+                                                      const int32_t *gate) {
   __shared__ float red[4];
+  AE_GATE(gate);
   const float *xr = x + (size_t)blockIdx.x * d;
   float ss = 0.f;
   for (int i = threadIdx.x * 4; i < d; i += 1024) {   // d is a multiple of 8
@@ -74,8 +76,9 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float *x, const floa
   }
 }
 
-void launch_rmsnorm(const float *x, const float *g, int rows, int d, float eps, float *out, hipStream_t s) {
-  rmsnorm_kernel<<<rows, 256, 0, s>>>(x, g, d, eps, out);
+void launch_rmsnorm(const float *x, const float *g, int rows, int d, float eps, float *out, hipStream_t s,
+                    const int32_t *gate) {
+  rmsnorm_kernel<<<rows, 256, 0, s>>>(x, g, d, eps, out, gate);
 }
 
 // ------------------------------------------------------------------ generic skinny GEMM
@@ -83,7 +86,9 @@ void launch_rmsnorm(const float *x, const float *g, int rows, int d, float eps, 
 // pieces.  The per-output summation order does not depend on the number of rows.
 template <typename WT, int MT>
 __global__ __launch_bounds__(256) void gemm_generic_kernel(const WT *W, int N, int K, const float *X, int ldx, int rows,
-                                                           const float *bias, float *Y, int ldy, int accumulate) {
+                                                           const float *bias, float *Y, int ldy, int accumulate,
+                                                           const int32_t *gate) {
+  AE_GATE(gate);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int n = blockIdx.x * 4 + wave;
   if (n >= N) return;
@@ -121,40 +126,43 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const WT *W, int N, i
 
 template <typename WT>
 static void gemm_generic_dispatch(const WT *W, int N, int K, const float *X, int ldx, int rows, const float *bias,
-                                  float *Y, int ldy, int acc, hipStream_t s) {
+                                  float *Y, int ldy, int acc, hipStream_t s, const int32_t *gate) {
   const dim3 grid((N + 3) / 4);
   if (rows <= 1)
-    gemm_generic_kernel<WT, 1><<<grid, 256, 0, s>>>(W, N, K, X, ldx, rows, bias, Y, ldy, acc);
+    gemm_generic_kernel<WT, 1><<<grid, 256, 0, s>>>(W, N, K, X, ldx, rows, bias, Y, ldy, acc, gate);
   else if (rows <= 4)
-    gemm_generic_kernel<WT, 4><<<grid, 256, 0, s>>>(W, N, K, X, ldx, rows, bias, Y, ldy, acc);
+    gemm_generic_kernel<WT, 4><<<grid, 256, 0, s>>>(W, N, K, X, ldx, rows, bias, Y, ldy, acc, gate);
   else
-    gemm_generic_kernel<WT, 16><<<grid, 256, 0, s>>>(W, N, K, X, ldx, rows, bias, Y, ldy, acc);
+    gemm_generic_kernel<WT, 16><<<grid, 256, 0, s>>>(W, N, K, X, ldx, rows, bias, Y, ldy, acc, gate);
 }
 
 void launch_gemm_generic(const void *W, int dtype, int N, int K, const float *X, int ldx, int rows,
-                         const float *bias, float *Y, int ldy, int accumulate, hipStream_t s) {
+                         const float *bias, float *Y, int ldy, int accumulate, hipStream_t s, const int32_t *gate) {
   if (dtype == AE_BF16)
-    gemm_generic_dispatch<bf16_t>((const bf16_t *)W, N, K, X, ldx, rows, bias, Y, ldy, accumulate, s);
+    gemm_generic_dispatch<bf16_t>((const bf16_t *)W, N, K, X, ldx, rows, bias, Y, ldy, accumulate, s, gate);
   else
-    gemm_generic_dispatch<float>((const float *)W, N, K, X, ldx, rows, bias, Y, ldy, accumulate, s);
+    gemm_generic_dispatch<float>((const float *)W, N, K, X, ldx, rows, bias, Y, ldy, accumulate, s, gate);
 }
 
 // ------------------------------------------------------------------ SwiGLU elementwise
-__global__ void silu_mul_kernel(const float *gate, const float *up, size_t n, float *out) {
+__global__ void silu_mul_kernel(const float *gate_proj, const float *up, size_t n, float *out, const int32_t *gate) {
+  AE_GATE(gate);
   for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
-    out[i] = silu_f(gate[i]) * up[i];
+    out[i] = silu_f(gate_proj[i]) * up[i];
 }
 
-void launch_silu_mul(const float *gate, const float *up, int rows, int f, float *out, hipStream_t s) {
+void launch_silu_mul(const float *gate_proj, const float *up, int rows, int f, float *out, hipStream_t s,
+                     const int32_t *gate) {
   const size_t n = (size_t)rows * f;
   const int blocks = (int)((n + 255) / 256 < 1024 ? (n + 255) / 256 : 1024);
-  silu_mul_kernel<<<blocks, 256, 0, s>>>(gate, up, n, out);
+  silu_mul_kernel<<<blocks, 256, 0, s>>>(gate_proj, up, n, out, gate);
 }
 
 // ------------------------------------------------------------------ argmax (lowest id wins ties)
-__global__ __launch_bounds__(1024) void argmax_kernel(const float *logits, int V, int32_t *out) {
+__global__ __launch_bounds__(1024) void argmax_kernel(const float *logits, int V, int32_t *out, const int32_t *gate) {
   __shared__ float bv[16];
   __shared__ int bi[16];
+  AE_GATE(gate);
   const float *x = logits + (size_t)blockIdx.x * V;
   float best = -INFINITY;
   int idx = 0x7fffffff;
@@ -177,15 +185,16 @@ __global__ __launch_bounds__(1024) void argmax_kernel(const float *logits, int V
   }
 }
 
-void launch_argmax(const float *logits, int rows, int V, int32_t *out_ids, hipStream_t s) {
-  argmax_kernel<<<rows, 1024, 0, s>>>(logits, V, out_ids);
+void launch_argmax(const float *logits, int rows, int V, int32_t *out_ids, hipStream_t s, const int32_t *gate) {
+  argmax_kernel<<<rows, 1024, 0, s>>>(logits, V, out_ids, gate);
 }
 
 // ------------------------------------------------------------------ draft head input
 // cat[r] = [feature row r ; embedding of the token that FOLLOWS slot r]  (Sec. 2.2)
 template <typename T>
 __global__ void draft_cat_kernel(const float *feat, int feat_ld, const T *emb, const int32_t *next_ids, int d,
-                                 float *cat) {
+                                 float *cat, const int32_t *gate) {
+  AE_GATE(gate);
   const int r = blockIdx.x;
   const T *e = emb + (size_t)next_ids[r] * d;
   for (int i = threadIdx.x; i < d; i += blockDim.x) {
@@ -195,25 +204,33 @@ __global__ void draft_cat_kernel(const float *feat, int feat_ld, const T *emb, c
 }
 
 void launch_draft_cat(const float *feat, int feat_ld, const void *emb, int dtype, const int32_t *next_ids, int rows,
-                      int d, float *cat, hipStream_t s) {
+                      int d, float *cat, hipStream_t s, const int32_t *gate) {
   if (dtype == AE_BF16)
-    draft_cat_kernel<bf16_t><<<rows, 256, 0, s>>>(feat, feat_ld, (const bf16_t *)emb, next_ids, d, cat);
+    draft_cat_kernel<bf16_t><<<rows, 256, 0, s>>>(feat, feat_ld, (const bf16_t *)emb, next_ids, d, cat, gate);
   else
-    draft_cat_kernel<float><<<rows, 256, 0, s>>>(feat, feat_ld, (const float *)emb, next_ids, d, cat);
+    draft_cat_kernel<float><<<rows, 256, 0, s>>>(feat, feat_ld, (const float *)emb, next_ids, d, cat, gate);
 }
 
 // ------------------------------------------------------------------ tiny control kernels
-__global__ void pick_draft_kernel(DevState *st, int i) {
+__global__ void pick_draft_kernel(DevState *st, int i, const int32_t *gate) {
+  AE_GATE(gate);
   int32_t t = st->argmax[0];
   if (st->override_ids[i] >= 0) t = st->override_ids[i];
   st->draft_ids[i] = t;
 }
-void launch_pick_draft(DevState *st, int i, int32_t *, hipStream_t s) { pick_draft_kernel<<<1, 1, 0, s>>>(st, i); }
+void launch_pick_draft(DevState *st, int i, hipStream_t s, const int32_t *gate) {
+  pick_draft_kernel<<<1, 1, 0, s>>>(st, i, gate);
+}
 
-// AdaEAGLE-DDD bookkeeping: log-probability of draft token i under softmax(logits), one
-// workgroup, fixed-shape reductions.
-__global__ __launch_bounds__(1024) void draft_logprob_kernel(const float *logits, int V, DevState *st, int i) {
+// AdaEAGLE-DDD bookkeeping behind draft token i (Sec. 3.4, 4.2): its log-probability under
+// softmax(logits / T) joins the running sum, the drafted length becomes i + 1, and the exit
+// rule for the next token is evaluated on the device: past the predicted length k the chain
+// goes on only while the sequence log-probability is at least theta (draft_live gates the
+// kernels of the tokens that follow).  One workgroup, fixed-shape reductions.
+__global__ __launch_bounds__(1024) void draft_logprob_kernel(const float *logits, int V, float inv_T, DevState *st, int i,
+                                                             int k, float theta, const int32_t *gate) {
   __shared__ float sh[1024];
+  AE_GATE(gate);
   const int t = threadIdx.x;
   float mx = -INFINITY;
   for (int x = t; x < V; x += 1024) mx = fmaxf(mx, logits[x]);
@@ -226,7 +243,7 @@ __global__ __launch_bounds__(1024) void draft_logprob_kernel(const float *logits
   mx = sh[0];
   __syncthreads();
   float se = 0.f;
-  for (int x = t; x < V; x += 1024) se += expf(logits[x] - mx);
+  for (int x = t; x < V; x += 1024) se += expf((logits[x] - mx) * inv_T);
   sh[t] = se;
   __syncthreads();
   for (int o = 512; o > 0; o >>= 1) {
@@ -234,13 +251,17 @@ __global__ __launch_bounds__(1024) void draft_logprob_kernel(const float *logits
     __syncthreads();
   }
   if (t == 0) {
-    const float lp = logits[st->draft_ids[i]] - mx - logf(sh[0]);
+    const float lp = (logits[st->draft_ids[i]] - mx) * inv_T - logf(sh[0]);
+    const float cum = (i == 0 ? 0.f : st->cum_logp) + lp;
     st->draft_lp[i] = lp;
-    st->cum_logp = (i == 0 ? 0.f : st->cum_logp) + lp;
+    st->cum_logp = cum;
+    st->draft_len = i + 1;
+    if (i + 1 >= k && !(cum >= theta)) st->draft_live = 0;
   }
 }
-void launch_draft_logprob(const float *logits, int V, DevState *st, int i, hipStream_t s) {
-  draft_logprob_kernel<<<1, 1024, 0, s>>>(logits, V, st, i);
+void launch_draft_logprob(const float *logits, int V, float T, DevState *st, int i, int k, float theta, hipStream_t s,
+                          const int32_t *gate) {
+  draft_logprob_kernel<<<1, 1024, 0, s>>>(logits, V, T > 0.f ? 1.0f / T : 1.0f, st, i, k, theta, gate);
 }
 
 __global__ void build_block_kernel(DevState *st, const int32_t *hist, int kv_len, int k) {
@@ -253,8 +274,8 @@ void launch_build_block(DevState *st, const int32_t *hist, int kv_len, int k, hi
 
 // Greedy acceptance (longest draft prefix equal to the target argmax, then the target's
 // own token) and the token-history side of the rollback.
-__global__ void accept_greedy_kernel(DevState *st, int32_t *hist, int kv_len, int rows) {
-  const int k = rows - 1;
+__global__ void accept_greedy_kernel(DevState *st, int32_t *hist, int kv_len, int rows, int k_on_device) {
+  const int k = k_on_device ? min(st->draft_len, rows - 1) : rows - 1;
   int acc = 0;
   while (acc < k && st->block[1 + acc] == st->argmax[acc]) ++acc;
   const int32_t bonus = st->argmax[acc];
@@ -263,8 +284,8 @@ __global__ void accept_greedy_kernel(DevState *st, int32_t *hist, int kv_len, in
   st->n_acc = acc;
   st->bonus = bonus;
 }
-void launch_accept_greedy(DevState *st, int32_t *hist, int kv_len, int rows, hipStream_t s) {
-  accept_greedy_kernel<<<1, 1, 0, s>>>(st, hist, kv_len, rows);
+void launch_accept_greedy(DevState *st, int32_t *hist, int kv_len, int rows, bool k_on_device, hipStream_t s) {
+  accept_greedy_kernel<<<1, 1, 0, s>>>(st, hist, kv_len, rows, k_on_device ? 1 : 0);
 }
 
 // ------------------------------------------------------------------ LDLP (Eq. 3)

@@ -64,6 +64,7 @@ void launch_retile(const void *rowmajor, int N, int K, void *tiled, int NBtot, i
 template <int EPI, bool NORM, int NACC, int NW, int D>
 __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(const GemmArgs a) {
   __shared__ f32x4 red[NW][NACC][64];
+  AE_GATE(a.gate);
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int g = lane >> 4, m = lane & 15;
   // a workgroup hanging over the end of the matrix slides back (recomputes, stores nothing new)
@@ -204,6 +205,7 @@ void launch_gemm_mfma(const GemmLaunch &L, hipStream_t s) {
   a.amax_val = L.amax_val; a.amax_idx = L.amax_idx;
   a.rope_tab = L.rope_tab; a.Kc = (uint16_t *)L.Kc; a.Vc = (uint16_t *)L.Vc;
   a.pos0 = L.pos0; a.n_ctx = L.n_ctx; a.hd = L.hd;
+  a.gate = L.gate;
   if (L.epi == EPI_QKV) {
     launch_shape<EPI_QKV, true>(a, s);
   } else if (L.epi == EPI_SWIGLU) {
@@ -219,9 +221,10 @@ void launch_gemm_mfma(const GemmLaunch &L, hipStream_t s) {
 // workgroup per row.  pick_i >= 0 (draft head, one row): also applies the caller's override
 // table and records draft token pick_i.
 __global__ __launch_bounds__(256) void argmax_finish_kernel(const float *val, const int32_t *idx, int NB, DevState *st,
-                                                            int pick_i) {
+                                                            int pick_i, const int32_t *gate) {
   __shared__ float bv[4];
   __shared__ int bi[4];
+  AE_GATE(gate);
   const int row = blockIdx.x;
   float best = -INFINITY;
   int best_i = 0x7fffffff;
@@ -250,8 +253,9 @@ __global__ __launch_bounds__(256) void argmax_finish_kernel(const float *val, co
   }
 }
 
-void launch_argmax_finish(const float *val, const int32_t *idx, int NB, int rows, DevState *st, int pick_i, hipStream_t s) {
-  argmax_finish_kernel<<<rows, 256, 0, s>>>(val, idx, NB, st, pick_i);
+void launch_argmax_finish(const float *val, const int32_t *idx, int NB, int rows, DevState *st, int pick_i, hipStream_t s,
+                          const int32_t *gate) {
+  argmax_finish_kernel<<<rows, 256, 0, s>>>(val, idx, NB, st, pick_i, gate);
 }
 
 // ------------------------------------------------------------------ packed-form producers
@@ -302,7 +306,8 @@ void launch_pack_rows(const float *src, int ld, int rows, int K, const float *ga
 
 // draft head input [feature ; embedding of the following token] -> packed, K = 2d
 __global__ void draft_cat_packed_kernel(const float *feat, int feat_ld, const uint16_t *emb, const int32_t *next_ids,
-                                        int d, u32x4 *Xp) {
+                                        int d, u32x4 *Xp, const int32_t *gate) {
+  AE_GATE(gate);
   const int r = blockIdx.x;
   const uint16_t *e = emb + (size_t)next_ids[r] * d;
   for (int k0 = threadIdx.x * 4; k0 < d; k0 += blockDim.x * 4) {
@@ -315,8 +320,8 @@ __global__ void draft_cat_packed_kernel(const float *feat, int feat_ld, const ui
 }
 
 void launch_draft_cat_packed(const float *feat, int feat_ld, const void *emb, const int32_t *next_ids, int rows, int d,
-                             void *Xp, hipStream_t s) {
-  draft_cat_packed_kernel<<<rows, 256, 0, s>>>(feat, feat_ld, (const uint16_t *)emb, next_ids, d, (u32x4 *)Xp);
+                             void *Xp, hipStream_t s, const int32_t *gate) {
+  draft_cat_packed_kernel<<<rows, 256, 0, s>>>(feat, feat_ld, (const uint16_t *)emb, next_ids, d, (u32x4 *)Xp, gate);
 }
 
 }  // namespace ae

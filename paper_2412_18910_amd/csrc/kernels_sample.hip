@@ -58,8 +58,9 @@ __device__ __forceinline__ const float *row_ptr(const float *tl, const float *dl
 
 // segstats[(row*S + seg)*2 + {0,1}] = (max, sum exp((l - max)/T)) of the segment; grid (S, rows)
 __global__ __launch_bounds__(kSegThreads) void seg_stats_kernel(const float *tl, const float *dl, int V, int n_target,
-                                                                double T, double *segstats) {
+                                                                double T, double *segstats, const int32_t *gate) {
   __shared__ double sh[kSegThreads];
+  AE_GATE(gate);
   const int seg = blockIdx.x, row = blockIdx.y, S = gridDim.x;
   const float *x = row_ptr(tl, dl, V, n_target, row);
   const int lo = seg * kSeg;
@@ -155,8 +156,10 @@ __device__ int inverse_cdf_final(const double *segtot, int S, const float *trow,
 // Draft token i ~ softmax(logits / T) by inverse CDF with st->u_draft[i]; result in st->argmax[0].
 // Segment totals of p follow from the segment statistics, no second pass over the logits.
 __global__ __launch_bounds__(kSeg) void sample_draft_final_kernel(const float *logits, int V, int S, double T,
-                                                                  const double *segstats, double *segtot, DevState *st, int i) {
+                                                                  const double *segstats, double *segtot, DevState *st, int i,
+                                                                  const int32_t *gate) {
   __shared__ double sh[2 * kSeg];
+  AE_GATE(gate);
   double mx, sum;
   combine_row(segstats, S, 0, T, sh, mx, sum);
   const int t = threadIdx.x;
@@ -172,22 +175,32 @@ size_t sample_scratch_doubles(int V) {
   return (size_t)2 * kMaxRows * S * 2 + 2 * kMaxRows * 2 + 2 * S + 16;
 }
 
-void launch_sample_draft(const float *logits, int V, float T, DevState *st, int i, double *scratch, hipStream_t s) {
+void launch_sample_draft(const float *logits, int V, float T, DevState *st, int i, double *scratch, hipStream_t s,
+                         const int32_t *gate) {
   const int S = (V + kSeg - 1) / kSeg;
   double *segstats = scratch, *segtot = scratch + (size_t)2 * kMaxRows * S * 2 + 2 * kMaxRows * 2;
-  seg_stats_kernel<<<dim3(S, 1), kSegThreads, 0, s>>>(logits, nullptr, V, 1, (double)T, segstats);
-  sample_draft_final_kernel<<<1, kSeg, 0, s>>>(logits, V, S, (double)T, segstats, segtot, st, i);
+  seg_stats_kernel<<<dim3(S, 1), kSegThreads, 0, s>>>(logits, nullptr, V, 1, (double)T, segstats, gate);
+  sample_draft_final_kernel<<<1, kSeg, 0, s>>>(logits, V, S, (double)T, segstats, segtot, st, i, gate);
 }
 
 // ------------------------------------------------------------------ acceptance + rollback bookkeeping
-// Rows: k+1 target rows then k draft rows.  Combines the row statistics, runs the accept tests
-// (thread 0, in order) and records the outcome: st->n_acc, and the (max, sum) pairs of target
-// row n_acc and, on a rejection, of draft row n_acc in rowstats[0..3].
-__global__ __launch_bounds__(kSeg) void accept_decide_kernel(const float *tl, const float *dl, int V, int S, int k, double T,
-                                                             const double *segstats, double *rowstats, DevState *st) {
+// Rows: kp+1 target rows then kp draft rows, kp = the draft tokens the block has room for; the
+// number actually drafted is k = kp, or st->draft_len when the block was padded (k_on_device).
+__device__ __forceinline__ int drafted(const DevState *st, int kp, int k_on_device) {
+  return k_on_device ? min(st->draft_len, kp) : kp;
+}
+
+// Combines the row statistics, runs the accept tests (thread 0, in order) and records the
+// outcome: st->n_acc, and the (max, sum) pairs of target row n_acc and, on a rejection, of
+// draft row n_acc in rowstats[0..3].
+__global__ __launch_bounds__(kSeg) void accept_decide_kernel(const float *tl, const float *dl, int V, int S, int kp,
+                                                             int k_on_device, double T, const double *segstats,
+                                                             double *rowstats, DevState *st) {
   __shared__ double sh[kSeg];
   __shared__ double rs[2 * kMaxRows][2];
-  for (int row = 0; row < 2 * k + 1; ++row) {
+  const int k = drafted(st, kp, k_on_device);
+  for (int row = 0; row < 2 * kp + 1; ++row) {
+    if ((row > k && row <= kp) || row > kp + k) continue;   // rows of tokens that were not drafted (uniform branch)
     double mx, sum;
     combine_row(segstats, S, row, T, sh, mx, sum);
     if (threadIdx.x == 0) { rs[row][0] = mx; rs[row][1] = sum; }
@@ -198,22 +211,24 @@ __global__ __launch_bounds__(kSeg) void accept_decide_kernel(const float *tl, co
     for (; acc < k; ++acc) {
       const int t = st->block[1 + acc];
       const double p = exp(((double)tl[(size_t)acc * V + t] - rs[acc][0]) / T) / rs[acc][1];
-      const double ph = exp(((double)dl[(size_t)acc * V + t] - rs[k + 1 + acc][0]) / T) / rs[k + 1 + acc][1];
+      const double ph = exp(((double)dl[(size_t)acc * V + t] - rs[kp + 1 + acc][0]) / T) / rs[kp + 1 + acc][1];
       double ratio = ph > 0.0 ? p / ph : 1.0;
       if (ratio > 1.0) ratio = 1.0;
       if (!(st->u_accept[acc] < ratio)) break;
     }
     st->n_acc = acc;
     rowstats[0] = rs[acc][0]; rowstats[1] = rs[acc][1];
-    rowstats[2] = acc < k ? rs[k + 1 + acc][0] : 0.0;
-    rowstats[3] = acc < k ? rs[k + 1 + acc][1] : 1.0;
+    rowstats[2] = acc < k ? rs[kp + 1 + acc][0] : 0.0;
+    rowstats[3] = acc < k ? rs[kp + 1 + acc][1] : 1.0;
   }
 }
 
 // segtot[s] = sum over segment s of q for the row the accept tests stopped at (grid S)
-__global__ __launch_bounds__(kSegThreads) void seg_total_kernel(const float *tl, const float *dl, int V, int k, double T,
-                                                                const double *rowstats, const DevState *st, double *segtot) {
+__global__ __launch_bounds__(kSegThreads) void seg_total_kernel(const float *tl, const float *dl, int V, int kp,
+                                                                int k_on_device, double T, const double *rowstats,
+                                                                const DevState *st, double *segtot) {
   __shared__ double sh[kSegThreads];
+  const int k = drafted(st, kp, k_on_device);
   const int acc = st->n_acc, mode = acc < k ? 1 : 0;
   const float *trow = tl + (size_t)acc * V, *drow = dl + (size_t)(acc < k ? acc : 0) * V;
   const double mt = rowstats[0], stt = rowstats[1], md = rowstats[2], sd = rowstats[3];
@@ -228,10 +243,12 @@ __global__ __launch_bounds__(kSegThreads) void seg_total_kernel(const float *tl,
 }
 
 // Draw of the bonus / resampled token and the rollback bookkeeping (one workgroup).
-__global__ __launch_bounds__(kSeg) void accept_final_kernel(const float *tl, const float *dl, int V, int S, int k, double T,
-                                                            const double *segstats, const double *rowstats, double *segtot,
-                                                            double *segtot2, DevState *st, int32_t *hist, int kv_len) {
+__global__ __launch_bounds__(kSeg) void accept_final_kernel(const float *tl, const float *dl, int V, int S, int kp,
+                                                            int k_on_device, double T, const double *segstats,
+                                                            const double *rowstats, double *segtot, double *segtot2,
+                                                            DevState *st, int32_t *hist, int kv_len) {
   __shared__ double sh[2 * kSeg];
+  const int k = drafted(st, kp, k_on_device);
   const int acc = st->n_acc, mode = acc < k ? 1 : 0;
   const float *trow = tl + (size_t)acc * V, *drow = dl + (size_t)(acc < k ? acc : 0) * V;
   const double mt = rowstats[0], stt = rowstats[1], md = rowstats[2], sd = rowstats[3];
@@ -253,16 +270,17 @@ __global__ __launch_bounds__(kSeg) void accept_final_kernel(const float *tl, con
   }
 }
 
-void launch_accept_sample(const float *tl, const float *dl, int V, int k, float T, DevState *st, int32_t *hist, int kv_len,
-                          double *scratch, hipStream_t s) {
+void launch_accept_sample(const float *tl, const float *dl, int V, int k, bool k_on_device, float T, DevState *st,
+                          int32_t *hist, int kv_len, double *scratch, hipStream_t s) {
+  const int kd = k_on_device ? 1 : 0;
   const int S = (V + kSeg - 1) / kSeg;
   double *segstats = scratch;
   double *rowstats = scratch + (size_t)2 * kMaxRows * S * 2;
   double *segtot = rowstats + 2 * kMaxRows * 2, *segtot2 = segtot + S;
-  seg_stats_kernel<<<dim3(S, 2 * k + 1), kSegThreads, 0, s>>>(tl, dl, V, k + 1, (double)T, segstats);
-  accept_decide_kernel<<<1, kSeg, 0, s>>>(tl, dl, V, S, k, (double)T, segstats, rowstats, st);
-  seg_total_kernel<<<S, kSegThreads, 0, s>>>(tl, dl, V, k, (double)T, rowstats, st, segtot);
-  accept_final_kernel<<<1, kSeg, 0, s>>>(tl, dl, V, S, k, (double)T, segstats, rowstats, segtot, segtot2, st, hist, kv_len);
+  seg_stats_kernel<<<dim3(S, 2 * k + 1), kSegThreads, 0, s>>>(tl, dl, V, k + 1, (double)T, segstats, nullptr);
+  accept_decide_kernel<<<1, kSeg, 0, s>>>(tl, dl, V, S, k, kd, (double)T, segstats, rowstats, st);
+  seg_total_kernel<<<S, kSegThreads, 0, s>>>(tl, dl, V, k, kd, (double)T, rowstats, st, segtot);
+  accept_final_kernel<<<1, kSeg, 0, s>>>(tl, dl, V, S, k, kd, (double)T, segstats, rowstats, segtot, segtot2, st, hist, kv_len);
 }
 
 }  // namespace ae

@@ -5,6 +5,14 @@ fixed draft lengths, the draft-length oracle (k = the scripted acceptance length
 LDLP-chosen length: tau, tokens/s, time in the draft and target phases, N_draft / N_target /
 N_waste as defined for Table 2 of arxiv 2412.18910.  Only the shape of the trade-off is
 comparable with the paper: weights are random and acceptance is scripted.
+
+Two more rows run AdaEAGLE-DDD (Sec. 3.4: LDLP length, then keep drafting while the draft
+sequence's log-probability stays above a threshold) with the exit rule evaluated on the host
+(one synchronisation per decision past k) and on the device (no synchronisation inside the
+draft, skipped tokens cost empty launches, padded verify block).  The random-init head gives
+every token a near-uniform probability, so the paper's threshold of -0.6 would never extend a
+draft; the default threshold here is the log-probability of 3.5 tokens at the uniform rate,
+which extends short predicted lengths to 3-4 tokens.
 """
 import argparse
 import sys
@@ -19,6 +27,9 @@ def main():
     ap.add_argument("--context", type=int, default=2048)
     ap.add_argument("--tokens", type=int, default=256)
     ap.add_argument("--mean-accept", type=float, default=3.5)
+    ap.add_argument("--ddd-threshold", type=float, default=None,
+                    help="log-probability threshold of the DDD rows (default: -3.5 * ln(vocab))")
+    ap.add_argument("--no-ddd", action="store_true")
     args = ap.parse_args()
 
     import torch
@@ -45,7 +56,15 @@ def main():
 
     rows = [("Vanilla AR", "-", 1.0, ar_tok_s, None, None, None, 0, n_formal, 0)]
     modes = [("fixed", k) for k in (2, 3, 4, 5, 6)] + [("oracle", None), ("ldlp", None)]
+    theta = args.ddd_threshold if args.ddd_threshold is not None else -3.5 * float(np.log(cfg.vocab))
+    if not args.no_ddd:
+        modes += [("ddd-host", None), ("ddd-device", None)]
     for mode, kf in modes:
+        if mode == "ddd-host":     # same weights, exit rule switched on
+            eng.close()
+            eng = Engine(cfg.with_(ddd_enabled=1, ddd_threshold=theta), w)
+        if mode.startswith("ddd"):
+            eng.set_ddd_mode(Engine.DDD_DEVICE if mode == "ddd-device" else Engine.DDD_HOST)
         eng.prefill(ctx_ids)
         eng.set_profiling(True)
         cnt, pos, r = Counters(), 0, 0
@@ -53,7 +72,8 @@ def main():
         torch.cuda.synchronize(); t0 = time.perf_counter()
         while pos < args.tokens:
             k = kf if mode == "fixed" else (int(script[r]) if mode == "oracle" else eng.ldlp()[0])
-            ov = scripted_override(formal, pos, k, int(script[r]), cfg.vocab)
+            # the DDD rule may extend the draft up to k_max tokens: script all of them
+            ov = scripted_override(formal, pos, cfg.k_max if mode.startswith("ddd") else k, int(script[r]), cfg.vocab)
             kk, na, toks = eng.step(k_force=k, override_ids=ov)
             assert np.array_equal(toks, formal[pos:pos + na + 1]), "speculative output left the AR sequence"
             pt = eng.phase_times()
@@ -62,7 +82,9 @@ def main():
         torch.cuda.synchronize(); total = time.perf_counter() - t0
         eng.set_profiling(False)
         s = cnt.summary()
-        name = {"fixed": "fixed length", "oracle": "draft-length oracle", "ldlp": "LDLP (random weights)"}[mode]
+        name = {"fixed": "fixed length", "oracle": "draft-length oracle", "ldlp": "LDLP (random weights)",
+                "ddd-host": f"LDLP + DDD rule (theta {theta:.1f}), decided on the host",
+                "ddd-device": f"LDLP + DDD rule (theta {theta:.1f}), decided on the device"}[mode]
         rows.append((name, kf if kf else "dyn.", s["tau"], s["tokens"] / total, total * 1e3, t_draft / 1e3, t_target / 1e3,
                      s["N_draft"], s["N_target"], s["N_waste"]))
     eng.close()

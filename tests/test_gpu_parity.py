@@ -700,6 +700,132 @@ def test_ddd_exit_rule_matches_oracle(cfg0, seed):
     eng.close()
 
 
+def _logp64(logits, tok, T=1.0):
+    z = logits.astype(np.float64) / T
+    return float(z[int(tok)] - z.max() - np.log(np.exp(z - z.max()).sum()))
+
+
+@pytest.mark.parametrize("temperature", [0.0, 0.8], ids=["greedy", "T0.8"])
+def test_ddd_device_rule_matches_host_rule_and_oracle_fp32(temperature):
+    """AdaEAGLE-DDD with the exit rule evaluated on the device (no synchronisation inside the
+    draft, padded verify block, drafted length taken from the device by the accept kernels)
+    against the host-evaluated rule and the oracle: whole steps, greedy and temperature > 0
+    (the statistic is then the log-probability of the SAMPLED tokens under softmax(logits/T))."""
+    base = TINY.with_(temperature=temperature, ddd_enabled=1)
+    ids = synth.token_ids(40, base.vocab, 300)
+    n_steps = 10
+
+    def uni(r):
+        if temperature == 0.0:
+            return None, None
+        return synth.uniforms(base.k_max, 5000 + r), synth.uniforms(base.k_max + 1, 6000 + r)
+
+    # probe: cumulative log-probabilities at every depth with the rule switched off (-1e9)
+    probe, _ = make_oracle(base.with_(ddd_threshold=-1e9), 50)
+    probe.prefill(ids)
+    depth3 = []
+    for r in range(n_steps):
+        ud, ua = uni(r)
+        d = probe.draft(0, u_draft=ud)
+        assert len(d) == base.k_max
+        T = temperature if temperature > 0 else 1.0
+        depth3.append(sum(_logp64(probe.draft_logits(i), d[i], T) for i in range(3)))
+        probe.verify(n_rows=len(d) + 1)
+        probe.accept(ua[:len(d) + 1] if ua is not None else None)
+    srt = sorted(depth3)
+    theta = 0.5 * (srt[n_steps // 2 - 1] + srt[n_steps // 2])     # about half of the steps pass depth 3
+    assert min(abs(v - theta) for v in depth3) > 1e-3
+    cfg = base.with_(ddd_threshold=float(theta))
+    eng_h, orc, w = make_pair(cfg, 50)
+    from paper_2412_18910_amd.binding import Engine
+    from .gpu_helpers import to_device
+    eng_d = Engine(cfg, to_device(w))
+    eng_d.set_ddd_mode(Engine.DDD_DEVICE)
+    for m in (orc, eng_h, eng_d):
+        m.prefill(ids)
+    lens = []
+    for r in range(n_steps):
+        k = r % 4                                  # predicted lengths 0..3: the rule decides the rest
+        ud, ua = uni(r)
+        so = orc.step(k_force=k, u_draft=ud, u_accept=ua)
+        sh = eng_h.step(k_force=k, u_draft=ud, u_accept=ua)
+        sd = eng_d.step(k_force=k, u_draft=ud, u_accept=ua)
+        for got in (sh, sd):
+            assert got[:2] == so[:2] and np.array_equal(got[2], so[2]), (r, so, got)
+        lens.append(so[0])
+        assert abs(eng_d.draft_logprob - orc.draft_logprob) < 1e-3
+        assert eng_h.kv_len == eng_d.kv_len == orc.kv_len
+    assert any(l > (r % 4) for r, l in enumerate(lens)) and any(l < base.k_max for l in lens), lens
+    # un-padded use of the device rule: ae_draft with an id output synchronises and reports the length
+    ud, ua = uni(99)
+    want = orc.draft(1, u_draft=ud)
+    got = eng_d.draft(1, u_draft=ud)
+    assert np.array_equal(want, got)
+    orc.verify(n_rows=len(want) + 1)
+    eng_d.verify(n_rows=len(got) + 1)
+    assert orc.accept(ua[:len(want) + 1] if ua is not None else None) == \
+        eng_d.accept(ua[:len(got) + 1] if ua is not None else None)
+    with pytest.raises(AdaEagleError) as e:
+        eng_d.set_ddd_mode(7)
+    assert e.value.code == AE_EINVAL
+    for m in (eng_h, eng_d):
+        m.close()
+
+
+def test_ddd_device_rule_equals_host_rule_bf16_and_decides_next_to_the_threshold():
+    """bf16 path: (1) device-evaluated rule == host-evaluated rule, step for step (same kernels,
+    so tokens, lengths and logits are bit-identical); (2) the statistic the kernels keep equals a
+    float64 evaluation of the GPU's own draft logits to 1e-3; (3) thresholds placed 2e-3 below /
+    above that value make the chain continue / stop exactly there."""
+    from paper_2412_18910_amd.binding import Engine
+    from .gpu_helpers import to_device
+    base = MED_BF16.with_(ddd_enabled=1)
+    w = to_device(synth.make_weights(base, 60))
+    ids = synth.token_ids(60, base.vocab, 301)
+    probe = Engine(base.with_(ddd_threshold=-1e9), w)
+    probe.prefill(ids)
+    d = probe.draft(0)
+    assert len(d) == base.k_max
+    lps = [_logp64(probe.draft_logits(i), d[i]) for i in range(base.k_max)]
+    cums = np.cumsum(lps)
+    assert abs(probe.draft_logprob - cums[-1]) < 1e-3 * max(1.0, abs(cums[-1]) / 10)
+    probe.close()
+    for mode in (Engine.DDD_HOST, Engine.DDD_DEVICE):
+        for j in (0, 2, 4):                       # decision taken behind token j+1
+            for sign, want_len in ((-1, None), (+1, j + 1)):
+                theta = float(cums[j] + sign * 2e-3)
+                eng = Engine(base.with_(ddd_threshold=theta), w)
+                eng.set_ddd_mode(mode)
+                eng.prefill(ids)
+                got = eng.draft(1)
+                if want_len is None:              # threshold just below: the chain goes past token j+1
+                    assert len(got) >= j + 2, (mode, j, len(got))
+                    nxt = next((i for i in range(j + 1, base.k_max) if cums[i] < theta), base.k_max - 1)
+                    assert len(got) == min(nxt + 1, base.k_max)
+                else:                             # threshold just above: token j+1 is the last one
+                    assert len(got) == max(want_len, 1), (mode, j, len(got))
+                assert np.array_equal(got, d[:len(got)])
+                eng.close()
+    # whole steps, natural drafts: the two modes agree bit for bit
+    theta = float(np.median(cums[1:4]))
+    cfg = base.with_(ddd_threshold=theta)
+    eng_h, eng_d = Engine(cfg, w), Engine(cfg, w)
+    eng_d.set_ddd_mode(Engine.DDD_DEVICE)
+    eng_h.prefill(ids)
+    eng_d.prefill(ids)
+    lens = []
+    for r in range(10):
+        k = r % 5
+        sh, sd = eng_h.step(k_force=k), eng_d.step(k_force=k)
+        assert sh[:2] == sd[:2] and np.array_equal(sh[2], sd[2]), (r, sh, sd)
+        assert np.array_equal(eng_h.logits(sh[1]), eng_d.logits(sd[1]))
+        assert eng_h.draft_logprob == eng_d.draft_logprob
+        lens.append(sh[0])
+    assert len(set(l - r % 5 for r, l in enumerate(lens))) > 1, lens     # some steps extended, by different amounts
+    eng_h.close()
+    eng_d.close()
+
+
 EDGE_BF16 = Config(2, 256, 4, 2, 64, 512, 1024, dtype=BF16, k_max=15, n_ctx_max=1024, ldlp_hidden=64)
 
 
