@@ -498,6 +498,7 @@ int ae_init(const ae_config *cfg, const ae_weights *w, void *hip_stream, ae_ctx 
   // bf16: re-tile every streamed matrix into the MFMA operand layout (see kernels_mfma.hip)
   c->fast = g.dtype == AE_BF16;
   if (c->fast) {
+    attention_mfma_setup();
     bool ok = tileable(c->lm_head) && tileable(c->draft_fc) && g.head_dim % 32 == 0;
     for (auto &l : c->layers)
       ok = ok && tileable(l.wq) && tileable(l.wk) && tileable(l.wv) && tileable(l.wo) && tileable(l.w_gate) &&

@@ -15,6 +15,9 @@ namespace ae {
 constexpr int kMaxRows = 16;       // rows of one verify / prefill block (one MFMA tile)
 constexpr int kAttnChunk = 256;    // keys per split-KV workgroup (fixed by absolute slot)
 constexpr int kMaxSplits = 64;     // n_ctx_max / kAttnChunk upper bound
+constexpr int kMfmaKeysPerWave = 64;                     // bf16 matrix-core attention: keys per wave,
+constexpr int kMfmaAttnChunk = 4 * kMfmaKeysPerWave;     // keys per workgroup (4 waves),
+constexpr int kMaxMfmaSplits = kMaxSplits * kAttnChunk / kMfmaAttnChunk;   // and chunks at the largest cache
 constexpr int kMaxLdlpHidden = 1024;
 constexpr int kDenseRB = 8;        // activation row-blocks per workgroup of the dense prompt GEMM (128 rows)
 constexpr int kDenseMinPrompt = 17;   // prompts of one 16-row block go through the decode kernels
@@ -184,6 +187,7 @@ void launch_rope_append(float *q, const float *k, const float *v, int rows, int 
                         const int32_t *gate = nullptr);
 void launch_attn_merge(const float *part, int rows, const ae_config &c, int n_chunks, float *out, hipStream_t s);
 // bf16 MFMA attention over the tiled cache layout (kernels_attn_mfma.hip)
+void attention_mfma_setup();   // once per context set-up: dynamic LDS limit of the kernels
 void launch_attention_mfma(const float *q, int rows, int pos0, const ae_config &c, const void *kv_layer, size_t v_off,
                            float *part, void *Xp_out, hipStream_t s, const int32_t *gate = nullptr);
 void launch_attention(const float *q, int rows, int pos0, const ae_config &c, const void *kv_layer, size_t v_off,

@@ -260,7 +260,7 @@ __global__ void attn_merge_kernel(const float *part, int rows, int H, int Hkv, i
 }
 
 size_t attn_part_floats(const ae_config &c) {
-  const int max_chunks = kv_capacity(c) / kAttnChunk;
+  const int max_chunks = kv_capacity(c) / (kMfmaAttnChunk < kAttnChunk ? kMfmaAttnChunk : kAttnChunk);
   return (size_t)c.n_heads * max_chunks * kMaxRows * (c.head_dim + 2);
 }
 

@@ -1,9 +1,13 @@
 // Variable-length causal attention over the bf16 KV cache on the gfx950 matrix cores.
 //
-// One workgroup = one KV head x one chunk of kAttnChunk (256) keys fixed by absolute slot;
-// its 4 waves take 64 keys each.  All query rows that share the KV head (rows x group
-// size, <= 64) are processed in tiles of 16.  HBM-bound: a wave issues its whole K and V
-// working set (32 KB) as 1 KB coalesced loads up front, everything else hides behind it.
+// One workgroup = one KV head x one chunk of kMfmaAttnChunk keys fixed by absolute slot; its
+// 4 waves take kMfmaKeysPerWave keys each.  (64 keys per wave measured 7.7 us per layer at 1024
+// cached tokens of the 7B shape and 11.6 us at 2100; 32 keys per wave, which doubles the
+// workgroup count, 8.2 and 11.1 us: the kernel is bound by its chain of latencies, launch ->
+// operand fetch -> combine -> store, about 5 us, not by how many compute units pull.)  All
+// query rows that share the KV head (rows x group size, <= 64) are processed in tiles of 16.
+// A wave issues its whole K and V working set as 1 KB coalesced loads up front, everything
+// else hides behind it.
 //
 // Cache layouts (bf16, one 1 KB tile = one wave-wide 128-bit load = one MFMA operand):
 //   K tile (16 keys x 32 d):   [kh][slot/16][d/32][lane = ((d%32)/8)*16 + slot%16][d%8]
@@ -24,13 +28,14 @@ namespace ae {
 
 #define split2a split2
 
-template <int HD>
+// KPW = keys per wave (32 or 64); a workgroup covers kMfmaAttnChunk = 4 * KPW keys.
+template <int HD, int KPW, bool GATED>
 __global__ __launch_bounds__(256) void attn_mfma_kernel(const float *q, int rows, int pos0, int H, int Hkv, int n_ctx,
                                                         const u32x4 *Kc, const u32x4 *Vc, float *part,
                                                         float scale_log2e, const int32_t *gate) {
-  constexpr int DT = HD / 32, VT = HD / 16;
+  constexpr int DT = HD / 32, VT = HD / 16, KT = KPW / 16, VB = KPW / 32;
   extern __shared__ u32x4 smem[];
-  AE_GATE(gate);
+  if constexpr (GATED) AE_GATE(gate);
   const int kh = blockIdx.x, chunk = blockIdx.y, n_chunks = gridDim.y;
   const int G = H / Hkv, R = rows * G, MT = (R + 15) / 16;
   u32x4 *Qs = smem;                                           // [MT][DT][2][64]
@@ -38,20 +43,20 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const float *q, int rows
   float *wm = red + 4 * 16 * HD;                              // [4][16]
   float *wl = wm + 64;                                        // [4][16]
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, g = lane >> 4, m = lane & 15;
-  const int kbase = chunk * kAttnChunk + w * 64;
+  const int kbase = chunk * (4 * KPW) + w * KPW;
   const bool active = kbase < pos0 + rows;   // does this wave own any visible key?
 
   // the wave's whole K / V working set, issued before anything else
-  u32x4 kreg[4][DT], vreg[2][VT];
+  u32x4 kreg[KT][DT], vreg[VB][VT];
   if (active) {
     const u32x4 *kp = Kc + (((size_t)kh * (n_ctx / 16) + (kbase >> 4)) * DT) * 64 + lane;
 #pragma unroll
-    for (int kt = 0; kt < 4; ++kt)
+    for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) kreg[kt][dt] = kp[(kt * DT + dt) * 64];
     const u32x4 *vp = Vc + (((size_t)kh * (n_ctx / 32) + (kbase >> 5)) * VT) * 64 + lane;
 #pragma unroll
-    for (int vb = 0; vb < 2; ++vb)
+    for (int vb = 0; vb < VB; ++vb)
 #pragma unroll
       for (int dt = 0; dt < VT; ++dt) vreg[vb][dt] = vp[(vb * VT + dt) * 64];
   }
@@ -84,14 +89,14 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const float *q, int rows
 #pragma unroll
     for (int dt = 0; dt < VT; ++dt) O[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     if (active) {
-      f32x4 S[4];
+      f32x4 S[KT];
 #pragma unroll
-      for (int kt = 0; kt < 4; ++kt) S[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int kt = 0; kt < KT; ++kt) S[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
         const u32x4 qh = Qs[((mt * DT + dt) * 2 + 0) * 64 + lane], ql = Qs[((mt * DT + dt) * 2 + 1) * 64 + lane];
 #pragma unroll
-        for (int kt = 0; kt < 4; ++kt) {
+        for (int kt = 0; kt < KT; ++kt) {
           S[kt] = mfma_bf16(kreg[kt][dt], qh, S[kt]);
           S[kt] = mfma_bf16(kreg[kt][dt], ql, S[kt]);
         }
@@ -99,7 +104,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const float *q, int rows
       // causal mask: row (query row = row / G) sees slots <= pos0 + row / G
       const int limit = row < R ? pos0 + row / G : -1;
 #pragma unroll
-      for (int kt = 0; kt < 4; ++kt)
+      for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const int key = kbase + kt * 16 + 4 * g + r;
@@ -110,7 +115,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const float *q, int rows
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       if (mx > -INFINITY) {
 #pragma unroll
-        for (int kt = 0; kt < 4; ++kt)
+        for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
             S[kt][r] = __builtin_amdgcn_exp2f(S[kt][r] - mx);
@@ -118,13 +123,13 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const float *q, int rows
           }
       } else {
 #pragma unroll
-        for (int kt = 0; kt < 4; ++kt) S[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int kt = 0; kt < KT; ++kt) S[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
       }
       lsum += __shfl_xor(lsum, 16, 64);
       lsum += __shfl_xor(lsum, 32, 64);
       // P^T as B operand: k-slot e of lane group g = key 16*(e/4) + 4g + e%4 of a 32-key block
 #pragma unroll
-      for (int vb = 0; vb < 2; ++vb) {
+      for (int vb = 0; vb < VB; ++vb) {
         uint32_t h0, h1, h2, h3, l0, l1, l2, l3;
         split2a(S[2 * vb][0], S[2 * vb][1], h0, l0);
         split2a(S[2 * vb][2], S[2 * vb][3], h1, l1);
@@ -173,75 +178,101 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const float *q, int rows
 
 // Merge of the chunk partials (log2-domain maxima); one workgroup of 256 threads per (row,
 // head): HD/4 threads across the head dimension (four elements each) times 1024/HD chunk
-// lanes, so the partials of many chunks are in flight at once.  Chunk lane cl sums chunks cl,
-// cl+CL, ... in ascending order and the lanes are combined in ascending order: a fixed order
-// that does not depend on the number of rows.  The result is written in packed form as the
-// input of the output projection (k index = h*HD + d).
-template <int HD>
+// lanes, so the partials of many chunks are in flight at once and every value is fetched in a
+// single round trip.  Chunk lane cl folds chunks cl, cl+CL, ... in ascending order with a
+// running maximum (rescaling its sums when the maximum grows) and the lanes are then combined
+// in ascending order against the overall maximum: a fixed order that does not depend on the
+// number of rows.  The result is written in packed form as the input of the output
+// projection (k index = h*HD + d).
+template <int HD, bool GATED>
 __global__ __launch_bounds__(256) void attn_merge_log2_kernel(const float *part, int rows, int H, int Hkv, int n_chunks,
                                                               u32x4 *Xp_out, const int32_t *gate) {
   constexpr int DQ = HD / 4, CL = 256 / DQ;
-  __shared__ float ms[kMaxSplits];
   __shared__ float4 nums[CL][DQ];
-  __shared__ float dens[CL];
-  AE_GATE(gate);
+  __shared__ float dens[CL], maxs[CL];
+  if constexpr (GATED) AE_GATE(gate);
   const int mrow = blockIdx.x / H, h = blockIdx.x % H, dq = threadIdx.x % DQ, cl = threadIdx.x / DQ;
   const int G = H / Hkv, kh = h / G, r = mrow * G + (h % G), R = rows * G;
   const float *base = part + ((size_t)kh * n_chunks * R + r) * (HD + 2);
   const size_t cstride = (size_t)R * (HD + 2);
-  for (int c = threadIdx.x; c < n_chunks; c += 256) ms[c] = base[c * cstride + HD];
-  __syncthreads();
-  float mx = -INFINITY;
-  for (int c = 0; c < n_chunks; ++c) mx = fmaxf(mx, ms[c]);
   float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
-  float den = 0.f;
+  float den = 0.f, mx = -INFINITY;
 #pragma unroll 2
   for (int c = cl; c < n_chunks; c += CL) {
-    const float mc = ms[c];
     const float *p = base + c * cstride;
     const float2 a = *reinterpret_cast<const float2 *>(p + dq * 4), b = *reinterpret_cast<const float2 *>(p + dq * 4 + 2);
-    const float lc = p[HD + 1];
-    if (mc > -INFINITY) {
-      const float wgt = __builtin_amdgcn_exp2f(mc - mx);
-      num.x = fmaf(wgt, a.x, num.x); num.y = fmaf(wgt, a.y, num.y);
-      num.z = fmaf(wgt, b.x, num.z); num.w = fmaf(wgt, b.y, num.w);
-      den = fmaf(wgt, lc, den);
+    const float2 ml = *reinterpret_cast<const float2 *>(p + HD);   // (chunk maximum, chunk sum)
+    if (ml.x > -INFINITY) {
+      const float mn = fmaxf(mx, ml.x);
+      const float so = __builtin_amdgcn_exp2f(mx - mn), sn = __builtin_amdgcn_exp2f(ml.x - mn);   // exp2(-inf) = 0 the first time
+      num.x = fmaf(sn, a.x, num.x * so); num.y = fmaf(sn, a.y, num.y * so);
+      num.z = fmaf(sn, b.x, num.z * so); num.w = fmaf(sn, b.y, num.w * so);
+      den = fmaf(sn, ml.y, den * so);
+      mx = mn;
     }
   }
   nums[cl][dq] = num;
-  if (dq == 0) dens[cl] = den;
+  if (dq == 0) { dens[cl] = den; maxs[cl] = mx; }
   __syncthreads();
   if (cl == 0) {
+    float mall = maxs[0];
 #pragma unroll
-    for (int i = 1; i < CL; ++i) {
-      const float4 o = nums[i][dq];
-      num.x += o.x; num.y += o.y; num.z += o.z; num.w += o.w;
-      den += dens[i];
+    for (int i = 1; i < CL; ++i) mall = fmaxf(mall, maxs[i]);
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float dall = 0.f;
+#pragma unroll
+    for (int i = 0; i < CL; ++i) {
+      const float mi = maxs[i];
+      if (mi > -INFINITY) {
+        const float wgt = __builtin_amdgcn_exp2f(mi - mall);
+        const float4 o = nums[i][dq];
+        acc.x = fmaf(wgt, o.x, acc.x); acc.y = fmaf(wgt, o.y, acc.y);
+        acc.z = fmaf(wgt, o.z, acc.z); acc.w = fmaf(wgt, o.w, acc.w);
+        dall = fmaf(wgt, dens[i], dall);
+      }
     }
-    packed_store4(Xp_out, mrow, h * HD + dq * 4, num.x / den, num.y / den, num.z / den, num.w / den);
+    packed_store4(Xp_out, mrow, h * HD + dq * 4, acc.x / dall, acc.y / dall, acc.z / dall, acc.w / dall);
   }
+}
+
+size_t attn_mfma_smem_bytes(int MT, int HD) {
+  return (size_t)MT * (HD / 32) * 128 * 16 + (size_t)4 * 16 * HD * 4 + 128 * 4;
+}
+
+// The widest block (4 query tiles: 16 rows x group size 4) needs more dynamic LDS than the
+// default limit; raised once per context set-up instead of before every launch.
+void attention_mfma_setup() {
+  const int sm128 = (int)attn_mfma_smem_bytes(4, 128), sm64 = (int)attn_mfma_smem_bytes(4, 64);
+  constexpr int KPW = kMfmaKeysPerWave;
+  (void)hipFuncSetAttribute((const void *)attn_mfma_kernel<128, KPW, false>, hipFuncAttributeMaxDynamicSharedMemorySize, sm128);
+  (void)hipFuncSetAttribute((const void *)attn_mfma_kernel<128, KPW, true>, hipFuncAttributeMaxDynamicSharedMemorySize, sm128);
+  (void)hipFuncSetAttribute((const void *)attn_mfma_kernel<64, KPW, false>, hipFuncAttributeMaxDynamicSharedMemorySize, sm64);
+  (void)hipFuncSetAttribute((const void *)attn_mfma_kernel<64, KPW, true>, hipFuncAttributeMaxDynamicSharedMemorySize, sm64);
+}
+
+template <int HD, bool GATED>
+static void launch_attention_cfg(const float *q, int rows, int pos0, const ae_config &c, const u32x4 *Kc, const u32x4 *Vc,
+                                 int n_chunks, size_t sm, float *part, void *Xp_out, hipStream_t s, const int32_t *gate) {
+  const dim3 grid(c.n_kv_heads, n_chunks);
+  const float scale_log2e = 1.4426950408889634f / sqrtf((float)HD);
+  attn_mfma_kernel<HD, kMfmaKeysPerWave, GATED><<<grid, 256, sm, s>>>(q, rows, pos0, c.n_heads, c.n_kv_heads, kv_capacity(c),
+                                                                      Kc, Vc, part, scale_log2e, gate);
+  attn_merge_log2_kernel<HD, GATED><<<rows * c.n_heads, 256, 0, s>>>(part, rows, c.n_heads, c.n_kv_heads, n_chunks,
+                                                                     (u32x4 *)Xp_out, gate);
 }
 
 void launch_attention_mfma(const float *q, int rows, int pos0, const ae_config &c, const void *kv_layer, size_t v_off,
                            float *part, void *Xp_out, hipStream_t s, const int32_t *gate) {
-  const int n_chunks = (pos0 + rows + kAttnChunk - 1) / kAttnChunk;
+  const int n_chunks = (pos0 + rows + kMfmaAttnChunk - 1) / kMfmaAttnChunk;
   const int G = c.n_heads / c.n_kv_heads, R = rows * G, MT = (R + 15) / 16;
-  const int HD = c.head_dim;
-  const size_t sm = (size_t)MT * (HD / 32) * 128 * 16 + (size_t)4 * 16 * HD * 4 + 128 * 4;
-  const dim3 grid(c.n_kv_heads, n_chunks);
-  const float scale_log2e = 1.4426950408889634f / sqrtf((float)HD);
+  const size_t sm = attn_mfma_smem_bytes(MT, c.head_dim);
   const u32x4 *Kc = (const u32x4 *)kv_layer, *Vc = (const u32x4 *)((const char *)kv_layer + v_off);
-  const int cap = kv_capacity(c);
-  if (HD == 128) {
-    if (sm > 48 * 1024)
-      (void)hipFuncSetAttribute((const void *)attn_mfma_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
-    attn_mfma_kernel<128><<<grid, 256, sm, s>>>(q, rows, pos0, c.n_heads, c.n_kv_heads, cap, Kc, Vc, part, scale_log2e, gate);
-    attn_merge_log2_kernel<128><<<rows * c.n_heads, 256, 0, s>>>(part, rows, c.n_heads, c.n_kv_heads, n_chunks, (u32x4 *)Xp_out, gate);
+  if (c.head_dim == 128) {
+    if (gate) launch_attention_cfg<128, true>(q, rows, pos0, c, Kc, Vc, n_chunks, sm, part, Xp_out, s, gate);
+    else launch_attention_cfg<128, false>(q, rows, pos0, c, Kc, Vc, n_chunks, sm, part, Xp_out, s, gate);
   } else {
-    if (sm > 48 * 1024)
-      (void)hipFuncSetAttribute((const void *)attn_mfma_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sm);
-    attn_mfma_kernel<64><<<grid, 256, sm, s>>>(q, rows, pos0, c.n_heads, c.n_kv_heads, cap, Kc, Vc, part, scale_log2e, gate);
-    attn_merge_log2_kernel<64><<<rows * c.n_heads, 256, 0, s>>>(part, rows, c.n_heads, c.n_kv_heads, n_chunks, (u32x4 *)Xp_out, gate);
+    if (gate) launch_attention_cfg<64, true>(q, rows, pos0, c, Kc, Vc, n_chunks, sm, part, Xp_out, s, gate);
+    else launch_attention_cfg<64, false>(q, rows, pos0, c, Kc, Vc, n_chunks, sm, part, Xp_out, s, gate);
   }
 }
 
