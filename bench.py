@@ -3,7 +3,9 @@
 
 One "step" = LDLP -> draft chain -> verify -> accept+rollback (one iteration of Alg. 1)
 on a synthetic random-init model with 2048 tokens of context and scripted acceptance
-lengths (truncated geometric, mean 3.5).  Prints ONE JSON line.
+lengths (truncated geometric, mean 3.5).  Prints ONE JSON line.  The headline is the 7B
+loop; short loops at the 13B / 4096-token and 8B-GQA / 8192-token shapes ride along under
+"shapes" (greedy scripted acceptance, plus the accept-phase time of a temperature-1 step).
 """
 import argparse
 import json
@@ -30,13 +32,169 @@ def draft_bytes(cfg, n):
 
 
 def profiled_traffic():
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary."""
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary
+    (FETCH_SIZE + WRITE_SIZE runs; counters cannot be read from inside this process)."""
     import re
     try:
         text = open(os.path.join(ROOT, "profiles", "adaeagle_step_7b_bf16.md")).read()
         return int(re.search(r"TRAFFIC_BYTES_PER_LAUNCH[^=]*=\s*(\d+)", text).group(1))
     except Exception:
         return None
+
+
+def sync():
+    import torch
+    torch.cuda.synchronize()
+
+
+def copy_rate(dev, mib=512, reps=6):
+    """Plain device-to-device copy of `mib` MiB: GB/s of bytes read + bytes written.  The
+    streaming rate this part sustains on the simplest possible kernel, measured in the same
+    process as everything else."""
+    import torch
+    src = torch.empty(mib << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    sync(); t0 = time.perf_counter()
+    for _ in range(reps):
+        dst.copy_(src)
+    sync(); dt = (time.perf_counter() - t0) / reps
+    del src, dst
+    torch.cuda.empty_cache()
+    return 2 * (mib << 20) / dt / 1e9
+
+
+def run_loop(preset, context, K, W, T, want_kernel_timing=True):
+    """The timed region for one shape: W warm-up steps, then exactly K ae_step calls bracketed
+    by device synchronisation; afterwards the same steps again with phase events (and per-launch
+    events on the gate/up GEMM).  Returns (results dict, engine, cfg, weights)."""
+    import numpy as np
+    import torch
+    from paper_2412_18910_amd import synth
+    from paper_2412_18910_amd.binding import Engine
+    from paper_2412_18910_amd.config import PRESETS
+    from paper_2412_18910_amd.loop import Counters, run_scripted, scripted_override
+
+    n_formal = (2 * K + W + 2) * (PRESETS[preset].k_max + 1) + 64
+    cfg = PRESETS[preset].with_(temperature=T)
+    cfg = cfg.with_(n_ctx_max=context + n_formal + 64)
+    w = synth.make_weights(cfg, 1, device="cuda:0")
+    eng = Engine(cfg, w)
+    ctx_ids = synth.token_ids(context, cfg.vocab, 11)
+    script = synth.truncated_geometric(4 * (K + W) + 8, 3.5, cfg.k_max, 5)
+    phase = {"ldlp": 0.0, "draft": 0.0, "verify": 0.0, "accept": 0.0}
+    kt_us, kt_n = 0.0, 0
+
+    if T > 0:
+        # temperature > 0: tokens are drawn (inverse CDF, seeded uniforms); the random-init head's own acceptance
+        def u(n, seed):
+            return synth.uniforms(n, seed)
+        eng.prefill(ctx_ids)
+        for i in range(8):
+            eng.verify([eng.pending]); eng.accept(u(1, 50 + i))
+        n_ar_timed = 64
+        sync(); t0 = time.perf_counter()
+        for i in range(n_ar_timed):
+            eng.verify([eng.pending]); eng.accept(u(1, 100 + i))
+        sync(); ar_tok_s = n_ar_timed / (time.perf_counter() - t0)
+        eng.prefill(ctx_ids)
+        for r in range(W):
+            eng.step(u_draft=u(cfg.k_max, 1000 + r), u_accept=u(cfg.k_max + 1, 2000 + r))
+        cnt = Counters()
+        us = [(u(cfg.k_max, 3000 + r), u(cfg.k_max + 1, 4000 + r)) for r in range(2 * K)]
+        emitted = 0
+        sync(); t0 = time.perf_counter()
+        for r in range(K):
+            k, na, toks = eng.step(u_draft=us[r][0], u_accept=us[r][1])
+            cnt.add(k, na)
+            emitted += na + 1
+        sync(); dt = time.perf_counter() - t0
+        eng.set_profiling(True)
+        if want_kernel_timing:
+            eng.set_kernel_timing(True)
+        for r in range(K, 2 * K):
+            eng.step(u_draft=us[r][0], u_accept=us[r][1])
+            for key, v in eng.phase_times().items():
+                phase[key] += v
+    else:
+        # plain autoregressive decoding on the same kernels: formal sequence + AR baseline
+        eng.prefill(ctx_ids)
+        first = eng.pending
+        formal = np.zeros(n_formal, np.int64)
+        n_ar_timed = min(128, n_formal - 8)
+        for i in range(8):
+            eng.verify([eng.pending]); formal[i] = eng.accept()[1]
+        sync(); t0 = time.perf_counter()
+        for i in range(8, 8 + n_ar_timed):
+            eng.verify([eng.pending]); formal[i] = eng.accept()[1]
+        sync(); ar_s = time.perf_counter() - t0
+        for i in range(8 + n_ar_timed, n_formal):
+            eng.verify([eng.pending]); formal[i] = eng.accept()[1]
+        ar_tok_s = n_ar_timed / ar_s
+
+        # the timed region: W warm-up steps then exactly K steps of the whole hot path
+        eng.prefill(ctx_ids)
+        assert eng.pending == first
+        pos = 0
+        _, pos = run_scripted(eng, formal, pos, W, script)
+        cnt = Counters()
+        sync(); t0 = time.perf_counter()
+        emitted, pos = run_scripted(eng, formal, pos, K, script[W:], counters=cnt)
+        sync(); dt = time.perf_counter() - t0
+
+        # same steps again with phase events and per-launch events on the dominant kernel
+        eng.prefill(ctx_ids)
+        pos2 = 0
+        _, pos2 = run_scripted(eng, formal, pos2, W, script)
+        eng.set_profiling(True)
+        if want_kernel_timing:
+            eng.set_kernel_timing(True)
+        for r in range(K):
+            k, _ = eng.ldlp()
+            ov = scripted_override(formal, pos2, k, int(script[W + r]), cfg.vocab)
+            kk, na, toks = eng.step(k_force=k, override_ids=ov)
+            pos2 += na + 1
+            for key, v in eng.phase_times().items():
+                phase[key] += v
+    if want_kernel_timing:
+        kt_us, kt_n = eng.kernel_timing()
+        eng.set_kernel_timing(False)
+    eng.set_profiling(False)
+
+    tok_s = emitted / dt
+    ms_per_step = dt / K * 1e3
+    n_mid = context + emitted // 2
+    vbytes, _ = verify_bytes(cfg, n_mid)
+    verify_us = phase["verify"] / K
+    verify_gbps = vbytes / (verify_us * 1e-6) / 1e9
+    res = {
+        "tokens_per_s": round(tok_s, 2), "ms_per_step": round(ms_per_step, 4), "steps": K,
+        "phase_us": {k: round(v / K, 1) for k, v in phase.items()},
+        "counters": cnt.summary(),
+        "ar_tokens_per_s": round(ar_tok_s, 2), "speedup_vs_ar": round(tok_s / ar_tok_s, 3),
+        "verify": {"us": round(verify_us, 1), "bytes": vbytes, "GBps": round(verify_gbps, 1),
+                   "frac_of_8TBps": round(verify_gbps / 8000, 3)},
+        "draft_us_per_token": round(phase["draft"] / max(cnt.n_draft, 1), 1),
+    }
+    return res, eng, cfg, w, ctx_ids, (kt_us, kt_n)
+
+
+def shape_line(preset, context, K, W):
+    """Short greedy loop at another workload shape, plus the accept-phase time at temperature 1
+    (float64 rejection-sampling kernels over the whole vocabulary)."""
+    import torch
+    res, eng, cfg, w, _, _ = run_loop(preset, context, K, W, 0.0, want_kernel_timing=False)
+    eng.close()
+    del eng, w
+    torch.cuda.empty_cache()
+    rt, eng, cfg, w, _, _ = run_loop(preset, context, max(K // 2, 4), 2, 1.0, want_kernel_timing=False)
+    eng.close()
+    del eng, w
+    torch.cuda.empty_cache()
+    res["workload"] = f"{preset}-shaped loop, bs=1, context {context}, k_max {cfg.k_max}, scripted acceptance (mean 3.5), greedy"
+    res["temperature1"] = {"accept_phase_us": rt["phase_us"]["accept"], "ms_per_step": rt["ms_per_step"],
+                           "note": "natural acceptance of the random-init head (~0): times the sampling kernels, not a speed-up"}
+    return res
 
 
 def main():
@@ -49,6 +207,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prompt-pass timing")
+    ap.add_argument("--no-shapes", action="store_true", help="skip the short loops at the 13B and 8B-GQA shapes")
     ap.add_argument("--temperature", type=float, default=0.0,
                     help="> 0: rejection sampling with seeded uniforms and the natural acceptance of the random-init "
                          "draft head instead of the greedy loop under scripted acceptance")
@@ -64,119 +223,19 @@ def main():
     import torch
     from paper_2412_18910_amd import synth
     from paper_2412_18910_amd.binding import Engine
-    from paper_2412_18910_amd.config import PRESETS
-    from paper_2412_18910_amd.loop import Counters, run_scripted
 
     K, W = args.steps, args.warmup
-    n_formal = (2 * K + W + 2) * 9 + 64
     T = args.temperature
-    cfg = PRESETS[args.preset].with_(temperature=T)
-    cfg = cfg.with_(n_ctx_max=args.context + n_formal + 64)
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    t_setup = time.time()
-    w = synth.make_weights(cfg, 1, device=dev)
-    eng = Engine(cfg, w)
-    ctx_ids = synth.token_ids(args.context, cfg.vocab, 11)
-    script = synth.truncated_geometric(4 * (K + W) + 8, 3.5, cfg.k_max, 5)
+    copy_gbps = copy_rate(dev)
 
-    def sync():
-        torch.cuda.synchronize()
-
-    if T > 0:
-        # ---- temperature > 0: tokens are drawn (inverse CDF, seeded uniforms); the draft head's own acceptance
-        def u(n, seed):
-            return synth.uniforms(n, seed)
-        eng.prefill(ctx_ids)
-        for i in range(8):
-            eng.verify([eng.pending]); eng.accept(u(1, 50 + i))
-        n_ar_timed = 128
-        sync(); t0 = time.perf_counter()
-        for i in range(n_ar_timed):
-            eng.verify([eng.pending]); eng.accept(u(1, 100 + i))
-        sync(); ar_tok_s = n_ar_timed / (time.perf_counter() - t0)
-        eng.prefill(ctx_ids)
-        for r in range(W):
-            eng.step(u_draft=u(cfg.k_max, 1000 + r), u_accept=u(cfg.k_max + 1, 2000 + r))
-        cnt = Counters()
-        phase = {"ldlp": 0.0, "draft": 0.0, "verify": 0.0, "accept": 0.0}
-        us = [(u(cfg.k_max, 3000 + r), u(cfg.k_max + 1, 4000 + r)) for r in range(2 * K)]
-        emitted = 0
-        sync(); t0 = time.perf_counter()
-        for r in range(K):
-            k, na, toks = eng.step(u_draft=us[r][0], u_accept=us[r][1])
-            cnt.add(k, na)
-            emitted += na + 1
-        sync(); dt = time.perf_counter() - t0
-        tok_s = emitted / dt
-        ms_per_step = dt / K * 1e3
-        eng.set_profiling(True)
-        eng.set_kernel_timing(True)
-        for r in range(K, 2 * K):
-            eng.step(u_draft=us[r][0], u_accept=us[r][1])
-            for key, v in eng.phase_times().items():
-                phase[key] += v
-        kt_us, kt_n = eng.kernel_timing()
-        eng.set_kernel_timing(False)
-        eng.set_profiling(False)
-    else:
-        # ---- plain autoregressive decoding on the same kernels: formal sequence + AR baseline
-        eng.prefill(ctx_ids)
-        first = eng.pending
-        formal = np.zeros(n_formal, np.int64)
-        n_ar_timed = min(128, n_formal - 8)
-        for i in range(8):
-            eng.verify([eng.pending]); formal[i] = eng.accept()[1]
-        sync(); t0 = time.perf_counter()
-        for i in range(8, 8 + n_ar_timed):
-            eng.verify([eng.pending]); formal[i] = eng.accept()[1]
-        sync(); ar_s = time.perf_counter() - t0
-        for i in range(8 + n_ar_timed, n_formal):
-            eng.verify([eng.pending]); formal[i] = eng.accept()[1]
-        ar_tok_s = n_ar_timed / ar_s
-
-        # ---- the timed region: W warm-up steps then exactly K steps of the whole hot path
-        eng.prefill(ctx_ids)
-        assert eng.pending == first
-        pos = 0
-        _, pos = run_scripted(eng, formal, pos, W, script)
-        cnt = Counters()
-        eng.set_profiling(True)
-        phase = {"ldlp": 0.0, "draft": 0.0, "verify": 0.0, "accept": 0.0}
-        eng.set_profiling(False)
-        sync(); t0 = time.perf_counter()
-        emitted, pos = run_scripted(eng, formal, pos, K, script[W:], counters=cnt)
-        sync(); dt = time.perf_counter() - t0
-        tok_s = emitted / dt
-        ms_per_step = dt / K * 1e3
-
-        # ---- same steps again with phase events and per-launch events on the dominant kernel
-        eng.prefill(ctx_ids)
-        pos2 = 0
-        _, pos2 = run_scripted(eng, formal, pos2, W, script)
-        eng.set_profiling(True)
-        eng.set_kernel_timing(True)
-        vocab = cfg.vocab
-        from paper_2412_18910_amd.loop import scripted_override
-        for r in range(K):
-            k, _ = eng.ldlp()
-            ov = scripted_override(formal, pos2, k, int(script[W + r]), vocab)
-            kk, na, toks = eng.step(k_force=k, override_ids=ov)
-            pos2 += na + 1
-            for key, v in eng.phase_times().items():
-                phase[key] += v
-        kt_us, kt_n = eng.kernel_timing()
-        eng.set_kernel_timing(False)
-        eng.set_profiling(False)
+    res, eng, cfg, w, ctx_ids, (kt_us, kt_n) = run_loop(args.preset, args.context, K, W, T)
     gate_up_bytes = 2 * 2 * cfg.d_ffn * cfg.d_model
     kern_us = kt_us / max(kt_n, 1)
     achieved = gate_up_bytes / (kern_us * 1e-6) / 1e9 if kt_n else 0.0
-    n_mid = args.context + emitted // 2
-    vbytes, wbytes = verify_bytes(cfg, n_mid)
-    verify_us = phase["verify"] / K
-    verify_gbps = vbytes / (verify_us * 1e-6) / 1e9
 
-    # ---- verify-only sweep (7B-shaped verify forward, cache pre-filled to 1024 tokens)
+    # ---- verify-only sweep (verify forward of 1..k_max+1 rows, cache pre-filled to 1024 tokens)
     sweep = {}
     if not args.no_sweep:
         feat = np.zeros(cfg.d_model, np.float32)
@@ -212,36 +271,44 @@ def main():
         n = args.context
         gemm_flops = 2 * n * (L * (2 * d * dq + 2 * d * dkv + 3 * d * f) + (2 * d * d + d * (dq + 2 * dkv)))
         attn_flops = 4 * L * dq * n * (n + 1) // 2
-        # every product runs twice on the matrix cores (bf16 hi and lo halves of the activations)
-        mfma_tflops = 2 * (gemm_flops + attn_flops) / (dense_ms * 1e-3) / 1e12
+        model_tflops = (gemm_flops + attn_flops) / (dense_ms * 1e-3) / 1e12
         prefill = {"tokens": n, "dense_ms": round(dense_ms, 2), "dense_tokens_per_s": round(n / dense_ms * 1e3, 1),
                    "blocks_ms": round(blocks_ms, 2), "speedup": round(blocks_ms / dense_ms, 2),
-                   "model_tflops": round((gemm_flops + attn_flops) / (dense_ms * 1e-3) / 1e12, 1),
-                   "roofline": {"bound": "mfma", "achieved": round(mfma_tflops, 1), "peak": 2500.0, "unit": "TFLOP/s",
-                                "frac": round(mfma_tflops / 2500.0, 4),
-                                "note": "whole prompt pass; issued bf16 MFMA flops = 2 x model flops (hi/lo split)"}}
+                   "model_tflops": round(model_tflops, 1),
+                   "roofline": {"bound": "mfma", "achieved": round(model_tflops, 1), "peak": 2500.0, "unit": "TFLOP/s",
+                                "frac": round(model_tflops / 2500.0, 4),
+                                "issued_tflops": round(2 * model_tflops, 1), "issued_frac": round(2 * model_tflops / 2500.0, 4),
+                                "note": "whole prompt pass; achieved = the method's own flops; every product is issued twice on "
+                                        "the matrix cores (bf16 hi and lo halves of the activations): issued = 2 x model"}}
+    eng.close()
+    del eng
+    torch.cuda.empty_cache()
 
     out = {
-        "metric": "adaeagle_decode_tokens_per_s_7b_bs1", "value": round(tok_s, 2), "unit": "tokens/s",
-        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 4),
+        "metric": "adaeagle_decode_tokens_per_s_7b_bs1", "value": res["tokens_per_s"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": res["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.preset}-shaped full AdaEAGLE loop (LDLP->draft->verify->accept), bs=1, "
                                f"context {args.context}, " + (f"temperature {T}, natural acceptance of the random-init draft head"
                                                               if T > 0 else "scripted acceptance (truncated geometric, mean 3.5)")
                                + f", k_max {cfg.k_max}",
                    "n_layers": cfg.n_layers, "d_model": cfg.d_model, "d_ffn": cfg.d_ffn, "vocab": cfg.vocab},
-        "step_us": round(ms_per_step * 1e3, 1),
-        "phase_us": {k: round(v / K, 1) for k, v in phase.items()},
-        "counters": cnt.summary(),
-        "ar_tokens_per_s": round(ar_tok_s, 2), "speedup_vs_ar": round(tok_s / ar_tok_s, 3),
-        "verify": {"us": round(verify_us, 1), "bytes": vbytes, "GBps": round(verify_gbps, 1),
-                   "frac_of_8TBps": round(verify_gbps / 8000, 3)},
+        "step_us": round(res["ms_per_step"] * 1e3, 1),
+        "phase_us": res["phase_us"],
+        "counters": res["counters"],
+        "ar_tokens_per_s": res["ar_tokens_per_s"], "speedup_vs_ar": res["speedup_vs_ar"],
+        "verify": res["verify"],
+        "draft_us_per_token": res["draft_us_per_token"],
         "verify_sweep_n1024": sweep,
         "prefill": prefill,
+        "copy_GBps": round(copy_gbps, 1),
         "roofline": {"bound": "hbm", "kernel": "gemm_mfma_kernel<EPI_SWIGLU, norm> (fused RMSNorm + gate/up + SwiGLU)",
                      "achieved": round(achieved, 1), "peak": 8000.0, "unit": "GB/s", "frac": round(achieved / 8000.0, 4),
                      "bytes_per_launch": gate_up_bytes, "avg_launch_us": round(kern_us, 2), "launches": kt_n,
-                     "traffic": profiled_traffic() if args.preset == "7b" else None},
+                     "timing": "HIP event pair around every launch on the launch stream (reads 2-3 us more than the "
+                               "kernel duration in a rocprofv3 trace: the pair also times the marker packets)",
+                     "traffic": profiled_traffic() if args.preset == "7b" else None,
+                     "traffic_source": "profiles/adaeagle_step_7b_bf16.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)"},
         "paper_context": "paper: 66.35 tok/s AdaEAGLE vs 39.36 AR (1.62x) on A800 fp32, Vicuna-7B, MT-Bench",
     }
 
@@ -251,14 +318,26 @@ def main():
         for _ in range(4):
             dst.copy_(src)
         sync()
+        del src, dst
 
-    # ---- CPU oracle on the host cores, bounded sample
+    # ---- CPU oracle on the host cores, bounded sample (same weights as the headline loop)
     if not args.no_cpu_baseline:
         try:
             out["cpu_baseline"] = cpu_baseline(cfg, w, synth)
         except Exception as e:  # the GPU result stands even if the host is too small
             out["cpu_baseline"] = {"value": None, "error": str(e)[:200]}
-    eng.close()
+    del w
+    torch.cuda.empty_cache()
+
+    # ---- the other two workload shapes, short loops (parity-test shapes; the 7B line stays the headline)
+    if not args.no_shapes and T == 0.0 and args.preset == "7b":
+        shapes = {}
+        for name, preset, context in (("13b_ctx4096", "13b", 4096), ("8b_gqa_ctx8192", "8b-gqa", 8192)):
+            try:
+                shapes[name] = shape_line(preset, context, 16, 3)
+            except Exception as e:
+                shapes[name] = {"error": str(e)[:200]}
+        out["shapes"] = shapes
     print(json.dumps(out))
 
 
@@ -266,7 +345,6 @@ def cpu_baseline(cfg, w, synth):
     """The CPU oracle as it stands, timed on a bounded sample: n_steps full steps (LDLP, k
     draft forwards, (k+1)-row verify, accept) at the same shape after a short random-filled
     context (CPU time is weight-bound and insensitive to the context length)."""
-    import numpy as np
     from oracle import binding as ob
     n_ctx, n_steps, k = 64, 8, 4
     ocfg = cfg.with_(n_ctx_max=n_ctx + 64).dict()

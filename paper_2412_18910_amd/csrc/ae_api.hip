@@ -623,6 +623,9 @@ int ae_prefill(ae_ctx *c, const int32_t *ids, int n) {
     for (int p0 = 0; p0 < n; p0 += kMaxRows) {
       const int rows = n - p0 < kMaxRows ? n - p0 : kMaxRows;
       const bool last = p0 + rows == n;
+      // keep the number of launches in flight bounded (a block is ~200 launches): tools that
+      // keep a record per outstanding dispatch have been seen to fail on tens of thousands
+      if (p0 > 0 && (p0 / kMaxRows) % 16 == 0) HIPCHK(c, hipStreamSynchronize(c->stream));
       target_forward(c, c->hist + p0, rows, p0, last ? rows - 1 : rows);
       const int drows = last ? rows - 1 : rows;  // slots whose next token is in the prompt
       if (drows > 0) draft_rows(c, c->F, g.d_model, c->hist + p0 + 1, drows, p0);

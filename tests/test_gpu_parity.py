@@ -643,6 +643,26 @@ def test_13b_shape_reduced_depth_step_matches_oracle():
     assert worst < 2e-2
 
 
+def test_13b_shape_full_depth_step_matches_oracle():
+    """All 40 layers of the 13B shape at its workload context (4096 cached tokens, 16 attention
+    chunks), one teacher-forced step with the widest block (k = k_max = 10, 11 rows)."""
+    from paper_2412_18910_amd.config import LLAMA_13B
+    cfg = LLAMA_13B.with_(n_ctx_max=4096 + 64)
+    worst = _full_size_step(cfg, 5, 4096, ks=[10])
+    print("13B full-depth max |dlogit| =", worst)
+    assert worst < 2e-2
+
+
+def test_8b_gqa_shape_full_depth_step_matches_oracle():
+    """All 32 layers of the 8B-GQA shape (4 query heads per KV head, 128256-token vocabulary) at
+    its workload context (8192 cached tokens, 32 attention chunks), greedy, k = k_max = 8."""
+    from paper_2412_18910_amd.config import LLAMA_8B_GQA
+    cfg = LLAMA_8B_GQA.with_(n_ctx_max=8192 + 64, temperature=0.0)
+    worst = _full_size_step(cfg, 6, 8192, ks=[8])
+    print("8B-GQA full-depth max |dlogit| =", worst)
+    assert worst < 2e-2
+
+
 @pytest.mark.parametrize("cfg0,seed", [(TINY, 12), (MED_BF16, 13)], ids=["fp32", "bf16"])
 def test_ddd_exit_rule_matches_oracle(cfg0, seed):
     """AdaEAGLE-DDD: the draft keeps going past the predicted length while the sequence
