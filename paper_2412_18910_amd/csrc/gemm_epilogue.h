@@ -46,12 +46,52 @@ __device__ __forceinline__ uint16_t f2bf_rne(float f) {
   return (uint16_t)(u >> 16);
 }
 
+// Values an epilogue reads from memory (old residual, gain, bias, rotary table).  The decode
+// GEMM requests them before its main loop (epi_prefetch) so that their latency hides behind the
+// weight stream instead of sitting at the very end of the kernel; the dense GEMM lets the
+// epilogue load them itself (pre == nullptr).
+struct EpiPre {
+  float4 a, b;
+};
+
+// Which segment (q | k | v, or the single output) row-block nb falls in, and its index there.
+__device__ __forceinline__ void epi_segment(const GemmArgs &a, int nb, int &si, int &nbs) {
+  si = 0; nbs = nb;
+  if (nb >= a.seg[0].nb_end) { si = 1; nbs = nb - a.seg[0].nb_end; }
+  if (nb >= a.seg[1].nb_end) { si = 2; nbs = nb - a.seg[1].nb_end; }
+}
+
+template <int EPI>
+__device__ __forceinline__ EpiPre epi_prefetch(const GemmArgs &a, int nb, int g, int m, bool row_ok) {
+  EpiPre p;
+  p.a = make_float4(0.f, 0.f, 0.f, 0.f);
+  p.b = make_float4(1.f, 1.f, 1.f, 1.f);
+  int si, nbs;
+  epi_segment(a, nb, si, nbs);
+  if (EPI == EPI_QKV) {
+    if (si < 2) {   // (cos, sin) of the lane's two rotary pairs at the row's slot
+      const int hd = a.hd, bph = hd >> 4, j = nbs % bph, slot = a.pos0 + (row_ok ? m : 0);
+      const int i0 = 8 * j + 4 * (g & 1);
+      p.a = *reinterpret_cast<const float4 *>(a.rope_tab + (size_t)slot * (hd >> 1) + i0);
+      p.b = *reinterpret_cast<const float4 *>(a.rope_tab + (size_t)slot * (hd >> 1) + i0 + 2);
+    }
+  } else if (EPI == EPI_RESID || EPI == EPI_STORE) {
+    const int n = nbs * 16 + g * 4;
+    if (row_ok) {
+      if (EPI == EPI_RESID) p.a = *reinterpret_cast<const float4 *>(a.seg[si].Y + (size_t)m * a.seg[si].ldy + n);
+      else if (a.bias && si == 0) p.a = *reinterpret_cast<const float4 *>(a.bias + n);
+      if (a.Xp_out && a.gain_out) p.b = *reinterpret_cast<const float4 *>(a.gain_out + n);
+    }
+  }
+  return p;
+}
+
 // s = accumulator of row-block nb (EPI_SWIGLU: the gate block, u = the up block nb + 1).
 // rb = row-block of the activations, the lane's row is rb*16 + m; kts = k-tile stride of the
 // packed output (pieces).  Every lane of the wave must call this (it shuffles).
 template <int EPI>
 __device__ __forceinline__ void epi_tile(const GemmArgs &a, f32x4 s, f32x4 u, int nb, int g, int m, int rb, bool row_ok,
-                                         float rinv, size_t kts) {
+                                         float rinv, size_t kts, const EpiPre *pre = nullptr) {
   const int row = rb * 16 + m;
   u32x4 *xpo = a.Xp_out + (size_t)rb * 128;
   if (EPI == EPI_SWIGLU) {
@@ -65,16 +105,15 @@ __device__ __forceinline__ void epi_tile(const GemmArgs &a, f32x4 s, f32x4 u, in
     // Row-blocks [0, seg0) = q, [seg0, seg1) = k (both with the rotary row order of
     // retile_kernel), [seg1, ..) = v.  q: rotate, store float in natural column order.
     // k: rotate, round to bf16, append to the tiled K cache.  v: round, append.
-    int si = 0, nbs = nb;
-    if (nb >= a.seg[0].nb_end) { si = 1; nbs = nb - a.seg[0].nb_end; }
-    if (nb >= a.seg[1].nb_end) { si = 2; nbs = nb - a.seg[1].nb_end; }
+    int si, nbs;
+    epi_segment(a, nb, si, nbs);
     const int hd = a.hd, bph = hd >> 4, head = nbs / bph, j = nbs % bph;
     const int slot = a.pos0 + (row_ok ? row : 0);
     float4 o = make_float4(s[0] * rinv, s[1] * rinv, s[2] * rinv, s[3] * rinv);
     if (si < 2) {
       const int i0 = 8 * j + 4 * (g & 1);   // rotary index of the pair, first-half coordinates
-      const float4 cs01 = *reinterpret_cast<const float4 *>(a.rope_tab + (size_t)slot * (hd >> 1) + i0);
-      const float4 cs23 = *reinterpret_cast<const float4 *>(a.rope_tab + (size_t)slot * (hd >> 1) + i0 + 2);
+      const float4 cs01 = pre ? pre->a : *reinterpret_cast<const float4 *>(a.rope_tab + (size_t)slot * (hd >> 1) + i0);
+      const float4 cs23 = pre ? pre->b : *reinterpret_cast<const float4 *>(a.rope_tab + (size_t)slot * (hd >> 1) + i0 + 2);
       const float sgn = g < 2 ? -1.f : 1.f;   // first half: a*c - b*s; second half: b*c + a*s
       const float p0 = __shfl_xor(o.x, 32, 64), p1 = __shfl_xor(o.y, 32, 64);
       const float p2 = __shfl_xor(o.z, 32, 64), p3 = __shfl_xor(o.w, 32, 64);
@@ -106,20 +145,19 @@ __device__ __forceinline__ void epi_tile(const GemmArgs &a, f32x4 s, f32x4 u, in
       a.Vc[base + 24] = f2bf_rne(o.w);
     }
   } else {
-    int si = 0, nbs = nb;
-    if (nb >= a.seg[0].nb_end) { si = 1; nbs = nb - a.seg[0].nb_end; }
-    if (nb >= a.seg[1].nb_end) { si = 2; nbs = nb - a.seg[1].nb_end; }
+    int si, nbs;
+    epi_segment(a, nb, si, nbs);
     const int n = nbs * 16 + g * 4;   // this lane holds columns n..n+3 of its row
     float4 o = make_float4(s[0] * rinv, s[1] * rinv, s[2] * rinv, s[3] * rinv);
     float ssq = 0.f;
     if (row_ok) {
       float *yp = a.seg[si].Y + (size_t)row * a.seg[si].ldy + n;
       if (a.bias && si == 0) {
-        const float4 b = *reinterpret_cast<const float4 *>(a.bias + n);
+        const float4 b = (pre && EPI == EPI_STORE) ? pre->a : *reinterpret_cast<const float4 *>(a.bias + n);
         o.x += b.x; o.y += b.y; o.z += b.z; o.w += b.w;
       }
       if (EPI == EPI_RESID) {
-        const float4 old = *reinterpret_cast<const float4 *>(yp);
+        const float4 old = pre ? pre->a : *reinterpret_cast<const float4 *>(yp);
         o.x += old.x; o.y += old.y; o.z += old.z; o.w += old.w;
       }
       if (EPI == EPI_RESID || a.seg[si].Y) *reinterpret_cast<float4 *>(yp) = o;
@@ -135,7 +173,7 @@ __device__ __forceinline__ void epi_tile(const GemmArgs &a, f32x4 s, f32x4 u, in
       if (a.Xp_out) {
         ssq = o.x * o.x + o.y * o.y + o.z * o.z + o.w * o.w;
         float4 gn = make_float4(1.f, 1.f, 1.f, 1.f);
-        if (a.gain_out) gn = *reinterpret_cast<const float4 *>(a.gain_out + n);
+        if (a.gain_out) gn = pre ? pre->b : *reinterpret_cast<const float4 *>(a.gain_out + n);
         packed_store4(xpo, m, n, o.x * gn.x, o.y * gn.y, o.z * gn.z, o.w * gn.w, kts);
       }
     }

@@ -85,6 +85,19 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(const GemmArgs a) {
 #pragma unroll
   for (int i = 0; i < NACC; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+  // what the epilogue of this wave's row-blocks will read (old residual, gain, bias, rotary
+  // table): requested now, consumed behind the main loop
+  constexpr int STEP = EPI == EPI_SWIGLU ? 2 : 1;
+  constexpr int NE = NACC / STEP >= NW ? (NACC / STEP + NW - 1) / NW : 1;   // row-blocks per wave in the epilogue
+  EpiPre pre[NE];
+  if (EPI != EPI_SWIGLU) {
+#pragma unroll
+    for (int e = 0; e < NE; ++e) {
+      const int rb = (w + e * NW) * STEP;
+      if (rb < NACC) pre[e] = epi_prefetch<EPI>(a, nb0 + rb, g, m, row_ok);
+    }
+  }
+
   u32x4 xb[D][2], wb[D][NACC];
   if (c0 < c1) {
 #pragma unroll
@@ -154,8 +167,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(const GemmArgs a) {
   __syncthreads();
   const float rinv = NORM ? rinv_s[xrow] : 1.f;
 
-  constexpr int STEP = EPI == EPI_SWIGLU ? 2 : 1;
-  for (int rb = w * STEP; rb < NACC; rb += NW * STEP) {
+#pragma unroll
+  for (int e = 0; e < NE; ++e) {
+    const int rb = (w + e * NW) * STEP;
+    if (rb >= NACC) break;
     const int nb = nb0 + rb;
     if (nb < (int)blockIdx.x * NACC) continue;   // slid-back duplicate of a neighbour's row-block
     f32x4 s = red[0][rb][lane];
@@ -167,7 +182,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_mfma_kernel(const GemmArgs a) {
 #pragma unroll
       for (int ww = 1; ww < NW; ++ww) u += red[ww][rb + 1][lane];
     }
-    epi_tile<EPI>(a, s, u, nb, g, m, 0, row_ok, rinv, 128);
+    epi_tile<EPI>(a, s, u, nb, g, m, 0, row_ok, rinv, 128, EPI != EPI_SWIGLU ? &pre[e] : nullptr);
   }
 }
 
