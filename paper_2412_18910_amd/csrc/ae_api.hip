@@ -139,7 +139,10 @@ void run_layer(ae_ctx *c, int li, float *x, int rows, int pos0, const float *nex
     if (timed) { hipEventRecord(c->kt_ev[c->kt_used + 1], s); c->kt_used += 2; }
     GemmLaunch dn;
     dn.W = &w.w_down; dn.Xp = c->xp_h; dn.rows = rows; dn.epi = EPI_RESID; dn.Y[0] = x; dn.ldy[0] = d; dn.seg_N[0] = d;
-    dn.Xp_out = c->xp_a; dn.gain_out = next_gain; dn.ssq_out = c->ssq_a;
+    // the draft layer's raw output is the first half of the next chained token's input [feature ;
+    // embedding] and the LM head's operand: it goes straight into that packed buffer
+    const bool draft_layer = li == g.n_layers;
+    dn.Xp_out = draft_layer ? c->xp_cat : c->xp_a; dn.gain_out = next_gain; dn.ssq_out = c->ssq_a;
     dn.gate = c->gate;
     launch_gemm_mfma(dn, s);
     c->Pa = Pd;
@@ -192,15 +195,21 @@ void target_forward(ae_ctx *c, const int32_t *ids_dev, int rows, int pos0, int l
 }
 
 // Draft head over `rows` slots from slot0: slot input = fc([feature ; emb(next token)]).
-// Leaves the head's outputs in x rows 0..rows-1.
-void draft_rows(ae_ctx *c, const float *feat, int feat_ld, const int32_t *next_ids_dev, int rows, int slot0) {
+// Leaves the head's outputs in x rows 0..rows-1 (bf16 path: also packed in xp_cat, first half).
+// chained_row >= 0 (bf16 path, one row): the input is already in row chained_row of xp_cat, the
+// head's previous output (left there by its down projection) and the embedding of the token
+// picked from it (left there by the kernel that picked it).
+void draft_rows(ae_ctx *c, const float *feat, int feat_ld, const int32_t *next_ids_dev, int rows, int slot0,
+                int chained_row = -1) {
   const ae_config &g = c->cfg;
   hipStream_t s = c->stream;
   const LayerW &dl = c->layers[g.n_layers];
   if (c->fast) {
-    launch_draft_cat_packed(feat, feat_ld, c->tok_emb, next_ids_dev, rows, g.d_model, c->xp_cat, s, c->gate);
+    if (chained_row < 0)
+      launch_draft_cat_packed(feat, feat_ld, c->tok_emb, next_ids_dev, rows, g.d_model, c->xp_cat, s, c->gate);
     GemmLaunch fc;
     fc.W = &c->draft_fc; fc.Xp = c->xp_cat; fc.rows = rows; fc.epi = EPI_STORE; fc.bias = c->draft_fc_b;
+    fc.row0 = chained_row < 0 ? 0 : chained_row;
     fc.Y[0] = c->x; fc.ldy[0] = g.d_model; fc.seg_N[0] = g.d_model;
     fc.Xp_out = c->xp_a; fc.gain_out = dl.attn_norm; fc.ssq_out = c->ssq_a;
     fc.gate = c->gate;
@@ -224,18 +233,22 @@ void draft_lm_head(ae_ctx *c, int row, int i) {
   const bool greedy = !(g.temperature > 0.f);
   if (c->fast) {
     GemmLaunch lm;
-    lm.W = &c->lm_head; lm.Xp = c->xp_a; lm.rows = 1; lm.row0 = row; lm.epi = EPI_STORE;
+    lm.W = &c->lm_head; lm.Xp = c->xp_cat; lm.rows = 1; lm.row0 = row; lm.epi = EPI_STORE;
     lm.Y[0] = dl; lm.ldy[0] = g.vocab; lm.seg_N[0] = g.vocab;
     if (greedy) { lm.amax_val = c->amax_val; lm.amax_idx = c->amax_idx; }
     lm.gate = c->gate;
     launch_gemm_mfma(lm, s);
+    DraftCat cat;   // the picked token's embedding joins the head's output in its packed input row
+    cat.emb = c->tok_emb; cat.Xp = c->xp_cat; cat.d = g.d_model; cat.row = row;
     if (greedy) {
-      launch_argmax_finish(c->amax_val, c->amax_idx, g.vocab / 16, 1, c->st, i, s, c->gate);   // argmax + override
-      return;
+      launch_argmax_finish(c->amax_val, c->amax_idx, g.vocab / 16, 1, c->st, i, s, c->gate, cat);   // argmax + override
+    } else {
+      launch_sample_draft(dl, g.vocab, g.temperature, c->st, i, c->prob, s, c->gate);
+      launch_pick_draft_packed(c->st, i, s, c->gate, cat);
     }
-  } else {
-    gemm(c, c->lm_head, c->x + (size_t)row * g.d_model, g.d_model, 1, nullptr, dl, g.vocab, 0);
+    return;
   }
+  gemm(c, c->lm_head, c->x + (size_t)row * g.d_model, g.d_model, 1, nullptr, dl, g.vocab, 0);
   if (greedy) launch_argmax(dl, 1, g.vocab, c->st->argmax, s, c->gate);
   else launch_sample_draft(dl, g.vocab, g.temperature, c->st, i, c->prob, s, c->gate);
   launch_pick_draft(c->st, i, s, c->gate);
@@ -499,6 +512,8 @@ int ae_init(const ae_config *cfg, const ae_weights *w, void *hip_stream, ae_ctx 
   c->fast = g.dtype == AE_BF16;
   if (c->fast) {
     attention_mfma_setup();
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) == hipSuccess) gemm_mfma_setup(cus);
     bool ok = tileable(c->lm_head) && tileable(c->draft_fc) && g.head_dim % 32 == 0;
     for (auto &l : c->layers)
       ok = ok && tileable(l.wq) && tileable(l.wk) && tileable(l.wv) && tileable(l.wo) && tileable(l.w_gate) &&
@@ -798,7 +813,7 @@ int ae_draft(ae_ctx *c, int k, const int32_t *override_ids, const double *u_draf
       }
     }
     if (i > 0) {  // chain: the head's previous output replaces the feature
-      draft_rows(c, fh, g.d_model, c->st->draft_ids + (i - 1), 1, n - 1 + i);
+      draft_rows(c, fh, g.d_model, c->st->draft_ids + (i - 1), 1, n - 1 + i, c->fast ? fh_row : -1);
       fh = c->x;
       fh_row = 0;
     }

@@ -238,8 +238,17 @@ struct GemmLaunch {
   const int32_t *gate = nullptr;  // see AE_GATE
 };
 void launch_gemm_mfma(const GemmLaunch &L, hipStream_t s);
+void gemm_mfma_setup(int num_cus);   // once per context set-up: compute-unit count for the shape table
+// Where the kernel that fixes a draft token leaves that token's embedding: row `row`, second
+// half (k = d .. 2d-1) of the draft head's packed input.  Xp == nullptr: nowhere.
+struct DraftCat {
+  const void *emb = nullptr;   // bf16 embedding table [V][d]
+  void *Xp = nullptr;
+  int d = 0, row = 0;
+};
 void launch_argmax_finish(const float *val, const int32_t *idx, int NB, int rows, DevState *st, int pick_i, hipStream_t s,
-                          const int32_t *gate = nullptr);
+                          const int32_t *gate = nullptr, DraftCat cat = DraftCat());
+void launch_pick_draft_packed(DevState *st, int i, hipStream_t s, const int32_t *gate, DraftCat cat);
 void launch_embed_packed(const void *emb, const int32_t *ids_dev, int rows, int d, const float *gain, float *x,
                          void *Xp, float *ssq, hipStream_t s);
 void launch_pack_rows(const float *src, int ld, int rows, int K, const float *gain, void *Xp, hipStream_t s);

@@ -200,10 +200,19 @@ static void launch_cfg(const GemmArgs &a, hipStream_t s) {
 // the K chunks dealt round-robin to the waves a shallow ring (2 k-tiles per wave) keeps the
 // band of the matrix that is being read narrow, which the wide shapes prefer (gate/up 31.2 ->
 // 30.8 us, QKV 19.6 -> 19.2 us, LM head 46.2 -> 43.4 us against the deeper rings).
+static int g_num_cus = 256;   // compute units of the device (gemm_mfma_setup)
+
+void gemm_mfma_setup(int num_cus) {
+  if (num_cus > 0) g_num_cus = num_cus;
+}
+
 template <int EPI, bool NORM>
 static void launch_shape(const GemmArgs &a, hipStream_t s) {
   if (EPI == EPI_SWIGLU) {
-    if (a.NBtot >= 1024) launch_cfg<EPI, NORM, 8, 4, 2>(a, s);
+    // 6 row-blocks per workgroup while that still gives at most one workgroup per compute unit
+    // (7B gate/up: 230 workgroups, 30.4 us against 30.7 with 8 row-blocks and 172 workgroups)
+    if (a.NBtot >= 1024 && (a.NBtot + 5) / 6 <= g_num_cus) launch_cfg<EPI, NORM, 6, 8, 2>(a, s);
+    else if (a.NBtot >= 1024) launch_cfg<EPI, NORM, 8, 4, 2>(a, s);
     else if (a.NBtot >= 512) launch_cfg<EPI, NORM, 4, 4, 4>(a, s);
     else launch_cfg<EPI, NORM, 2, 4, 4>(a, s);
   } else {
@@ -247,13 +256,26 @@ void launch_gemm_mfma(const GemmLaunch &L, hipStream_t s) {
   }
 }
 
+// Embedding of token t -> packed row `row`, k = k_off .. k_off + d - 1 (the second half of the
+// draft head's input [feature ; embedding of the next token]); all threads of the workgroup.
+__device__ __forceinline__ void pack_embedding(const uint16_t *emb, int32_t t, int d, u32x4 *Xp, int row, int k_off) {
+  const uint16_t *e = emb + (size_t)t * d;
+  for (int k0 = threadIdx.x * 4; k0 < d; k0 += blockDim.x * 4) {
+    const uint2 raw = *reinterpret_cast<const uint2 *>(e + k0);
+    packed_store4(Xp, row, k_off + k0, __uint_as_float(raw.x << 16), __uint_as_float(raw.x & 0xffff0000u),
+                  __uint_as_float(raw.y << 16), __uint_as_float(raw.y & 0xffff0000u));
+  }
+}
+
 // Final argmax over the LM head's row-block partials (lowest token id wins ties), one
 // workgroup per row.  pick_i >= 0 (draft head, one row): also applies the caller's override
-// table and records draft token pick_i.
+// table, records draft token pick_i and, when cat.Xp is set, writes that token's embedding into
+// the draft head's packed input row for the next chained forward.
 __global__ __launch_bounds__(256) void argmax_finish_kernel(const float *val, const int32_t *idx, int NB, DevState *st,
-                                                            int pick_i, const int32_t *gate) {
+                                                            int pick_i, const int32_t *gate, DraftCat cat) {
   __shared__ float bv[4];
   __shared__ int bi[4];
+  __shared__ int32_t tok_s;
   AE_GATE(gate);
   const int row = blockIdx.x;
   float best = -INFINITY;
@@ -280,12 +302,31 @@ __global__ __launch_bounds__(256) void argmax_finish_kernel(const float *val, co
       if (st->override_ids[pick_i] >= 0) t = st->override_ids[pick_i];
       st->draft_ids[pick_i] = t;
     }
+    tok_s = t;
+  }
+  if (pick_i >= 0 && cat.Xp) {
+    __syncthreads();
+    pack_embedding((const uint16_t *)cat.emb, tok_s, cat.d, (u32x4 *)cat.Xp, cat.row, cat.d);
   }
 }
 
 void launch_argmax_finish(const float *val, const int32_t *idx, int NB, int rows, DevState *st, int pick_i, hipStream_t s,
-                          const int32_t *gate) {
-  argmax_finish_kernel<<<rows, 256, 0, s>>>(val, idx, NB, st, pick_i, gate);
+                          const int32_t *gate, DraftCat cat) {
+  argmax_finish_kernel<<<rows, 256, 0, s>>>(val, idx, NB, st, pick_i, gate, cat);
+}
+
+// temperature > 0: the sampled token (st->argmax[0]) with the override table applied becomes draft
+// token i; its embedding goes into the draft head's packed input row like above
+__global__ __launch_bounds__(256) void pick_draft_packed_kernel(DevState *st, int i, const int32_t *gate, DraftCat cat) {
+  AE_GATE(gate);
+  int32_t t = st->argmax[0];
+  if (st->override_ids[i] >= 0) t = st->override_ids[i];
+  if (threadIdx.x == 0) st->draft_ids[i] = t;
+  pack_embedding((const uint16_t *)cat.emb, t, cat.d, (u32x4 *)cat.Xp, cat.row, cat.d);
+}
+
+void launch_pick_draft_packed(DevState *st, int i, hipStream_t s, const int32_t *gate, DraftCat cat) {
+  pick_draft_packed_kernel<<<1, 256, 0, s>>>(st, i, gate, cat);
 }
 
 // ------------------------------------------------------------------ packed-form producers
