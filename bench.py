@@ -229,6 +229,13 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     copy_gbps = copy_rate(dev)
+    # dependent chains of read-only streaming kernels at the byte counts of the decode GEMMs
+    # (o-proj 33.6 MB, down 90.2 MB / QKV 100.7 MB, gate/up 180.4 MB): the achievable yardstick
+    from paper_2412_18910_amd.binding import probe_read_stream
+    read_stream = {}
+    for mb in (32, 96, 192):
+        us = probe_read_stream(mb << 20)
+        read_stream[f"{mb}MiB"] = {"us_per_launch": round(us, 2), "GBps": round((mb << 20) / us / 1e3, 1)}
 
     res, eng, cfg, w, ctx_ids, (kt_us, kt_n) = run_loop(args.preset, args.context, K, W, T)
     gate_up_bytes = 2 * 2 * cfg.d_ffn * cfg.d_model
@@ -302,6 +309,7 @@ def main():
         "verify_sweep_n1024": sweep,
         "prefill": prefill,
         "copy_GBps": round(copy_gbps, 1),
+        "read_stream_chain": read_stream,
         "roofline": {"bound": "hbm", "kernel": "gemm_mfma_kernel<EPI_SWIGLU, norm> (fused RMSNorm + gate/up + SwiGLU)",
                      "achieved": round(achieved, 1), "peak": 8000.0, "unit": "GB/s", "frac": round(achieved / 8000.0, 4),
                      "bytes_per_launch": gate_up_bytes, "avg_launch_us": round(kern_us, 2), "launches": kt_n,

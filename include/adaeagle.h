@@ -32,6 +32,7 @@
 #ifndef ADAEAGLE_H
 #define ADAEAGLE_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -237,6 +238,15 @@ int ae_get_phase_times(ae_ctx *ctx, ae_phase_times *out);   /* of the last ae_st
  * stream; totals are folded in at every stream synchronisation.  Enabling resets them. */
 int ae_set_kernel_timing(ae_ctx *ctx, int enabled);
 int ae_get_kernel_timing(ae_ctx *ctx, double *total_us, int64_t *launches);
+
+/* Diagnostic yardstick for the bandwidth figures: runs `launches` plain read-only streaming
+ * kernels back to back on `hip_stream` (each reads bytes_per_launch bytes, a multiple of 4096,
+ * from device memory it allocates and frees itself; consecutive launches read different
+ * buffers), `repeats` times, and returns the mean wall time per launch in microseconds (host
+ * pointer).  This is what a dependent chain of kernels that do nothing but stream their operand
+ * sustains on the GPU: the decode GEMMs of this library (Eq. 1 / Eq. 2 forwards at batch size 1)
+ * are exactly such chains with arithmetic attached. */
+int ae_probe_read_stream(void *hip_stream, size_t bytes_per_launch, int launches, int repeats, double *us_per_launch);
 
 const char *ae_version(void);
 

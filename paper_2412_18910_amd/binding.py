@@ -22,7 +22,7 @@ EXPORTS = ("ae_init", "ae_free", "ae_last_error", "ae_prefill", "ae_kv_import", 
            "ae_draft", "ae_verify", "ae_accept", "ae_step", "ae_kv_len", "ae_pending", "ae_get_logits",
            "ae_get_feature", "ae_get_draft_logits", "ae_get_kv_row", "ae_set_profiling", "ae_get_phase_times",
            "ae_set_kernel_timing", "ae_get_kernel_timing", "ae_last_draft_len", "ae_get_draft_logprob", "ae_set_prefill_mode", "ae_version",
-           "ae_kv_import_static", "ae_ldlp_loss", "ae_set_ddd_mode")
+           "ae_kv_import_static", "ae_ldlp_loss", "ae_set_ddd_mode", "ae_probe_read_stream")
 
 
 class AeConfig(C.Structure):
@@ -106,12 +106,24 @@ def load_library(path=LIB_PATH):
         "ae_set_ddd_mode": (I, [P, I]),
         "ae_get_kernel_timing": (I, [P, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
         "ae_version": (C.c_char_p, []),
+        "ae_probe_read_stream": (I, [P, C.c_size_t, I, I, f64p]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
         fn.restype, fn.argtypes = res, args
     _lib = lib
     return lib
+
+
+def probe_read_stream(bytes_per_launch, launches=64, repeats=5, stream=None):
+    """Microseconds per launch of a dependent chain of read-only streaming kernels (diagnostic)."""
+    lib = load_library()
+    us = C.c_double()
+    rc = lib.ae_probe_read_stream(stream.cuda_stream if stream is not None else None, int(bytes_per_launch), launches,
+                                  repeats, C.byref(us))
+    if rc != AE_OK:
+        raise AdaEagleError(rc, "ae_probe_read_stream", "probe failed")
+    return us.value
 
 
 def _p(a, ct):

@@ -882,6 +882,17 @@ def test_context_lengths_around_tile_and_chunk_boundaries(n_ctx):
     eng.close()
 
 
+def test_read_stream_probe_reports_a_plausible_rate():
+    """The diagnostic yardstick of the bandwidth figures: a chain of read-only kernels."""
+    from paper_2412_18910_amd.binding import load_library, probe_read_stream
+    import ctypes as C
+    us = probe_read_stream(32 << 20, launches=16, repeats=2)
+    gbps = (32 << 20) / us / 1e3
+    assert 1000.0 < gbps < 8000.0, gbps          # between a seventh of the published HBM peak and the peak itself
+    out = C.c_double()
+    assert load_library().ae_probe_read_stream(None, 1000, 4, 1, C.byref(out)) == AE_EINVAL   # not a multiple of 4096
+
+
 def test_capacity_limits_are_enforced():
     cfg = EDGE_BF16.with_(n_ctx_max=64, k_max=7)
     eng, _, _ = make_pair(cfg, 22)
