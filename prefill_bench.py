@@ -1,15 +1,18 @@
 """Times the prompt pass (first iteration of Alg. 1) on one MI355X: dense chunk kernels against
 16-row blocks through the decode kernels, on a synthetic random-init model.
 
-    python3 -m paper_2412_18910_amd.prefill_bench [--preset 7b] [--tokens 2048] [--layers N]
-                                                  [--modes dense,blocks] [--reps 3] [--chunk 2048]
+    python3 prefill_bench.py [--preset 7b] [--tokens 2048] [--layers N] [--modes dense,blocks] [--reps 3] [--chunk 2048]
 
 Prints one line per mode and a JSON summary.  Also the workload of the rocprofv3 summaries of
 the dense kernels under profiles/.
 """
 import argparse
 import json
+import os
+import sys
 import time
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 
 
 def model_flops(cfg, n):
@@ -34,9 +37,9 @@ def main():
 
     import numpy as np
     import torch
-    from . import synth
-    from .binding import Engine
-    from .config import PRESETS
+    from paper_2412_18910_amd import synth
+    from paper_2412_18910_amd.binding import Engine
+    from paper_2412_18910_amd.config import PRESETS
 
     cfg = PRESETS[args.preset].with_(n_ctx_max=args.tokens + 64)
     if args.layers:

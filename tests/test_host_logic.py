@@ -8,16 +8,19 @@ import numpy as np
 from paper_2412_18910_amd import synth
 from paper_2412_18910_amd.config import LLAMA_13B, LLAMA_7B, LLAMA_8B_GQA, TINY
 from paper_2412_18910_amd.loop import Counters, generate, run_scripted, scripted_override
-from paper_2412_18910_amd.prefill_bench import model_flops
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _bench():
-    spec = importlib.util.spec_from_file_location("bench_mod", os.path.join(ROOT, "bench.py"))
+def _script(name):
+    spec = importlib.util.spec_from_file_location(name + "_mod", os.path.join(ROOT, name + ".py"))
     mod = importlib.util.module_from_spec(spec)
     spec.loader.exec_module(mod)
     return mod
+
+
+def _bench():
+    return _script("bench")
 
 
 def test_counters_follow_the_table2_definitions():
@@ -120,6 +123,7 @@ def test_prompt_pass_flops():
     per_layer = 4 * c.d_model * c.d_model + 3 * c.d_model * c.d_ffn
     draft = 2 * c.d_model * c.d_model + 3 * c.d_model * c.d_model      # fc [d, 2d] + fused q, k, v
     attn = 4 * c.n_layers * c.d_model * n * (n + 1) // 2
+    model_flops = _script("prefill_bench").model_flops
     assert model_flops(c, n) == 2 * n * (c.n_layers * per_layer + draft) + attn
     assert 26e12 < model_flops(c, n) < 29e12
 
