@@ -16,8 +16,7 @@ constexpr int kMaxRows = 16;       // rows of one verify / prefill block (one MF
 constexpr int kAttnChunk = 256;    // keys per split-KV workgroup (fixed by absolute slot)
 constexpr int kMaxSplits = 64;     // n_ctx_max / kAttnChunk upper bound
 constexpr int kMfmaKeysPerWave = 64;                     // bf16 matrix-core attention: keys per wave,
-constexpr int kMfmaAttnChunk = 4 * kMfmaKeysPerWave;     // keys per workgroup (4 waves),
-constexpr int kMaxMfmaSplits = kMaxSplits * kAttnChunk / kMfmaAttnChunk;   // and chunks at the largest cache
+constexpr int kMfmaAttnChunk = 4 * kMfmaKeysPerWave;     // keys per workgroup (4 waves)
 constexpr int kMaxLdlpHidden = 1024;
 constexpr int kDenseRB = 8;        // activation row-blocks per workgroup of the dense prompt GEMM (128 rows)
 constexpr int kDenseMinPrompt = 17;   // prompts of one 16-row block go through the decode kernels
@@ -104,7 +103,7 @@ struct ae_ctx {
   // bf16 fast path: packed activations (GEMM B operands) and RMSNorm partial sums
   void *xp_a = nullptr, *xp_f = nullptr, *xp_att = nullptr, *xp_h = nullptr, *xp_cat = nullptr;
   float *ssq_a = nullptr, *ssq_f = nullptr;
-  float *amax_val = nullptr;       // LM-head argmax partials [vocab/16][16]
+  float *amax_val = nullptr;       // LM-head argmax partials [16][vocab/16]
   int32_t *amax_idx = nullptr;
   int Pa = 0;                      // number of valid partial-sum rows in ssq_a
   double *prob = nullptr;          // T>0 scratch: segment / row statistics of the sampling kernels
@@ -229,7 +228,7 @@ struct GemmLaunch {
   void *Xp_out = nullptr;         // packed output for the next GEMM
   const float *gain_out = nullptr;
   float *ssq_out = nullptr;
-  float *amax_val = nullptr;      // LM head: per row-block argmax partials [N/16][16]
+  float *amax_val = nullptr;      // LM head: argmax partials per row and row-block [16][N/16]
   int32_t *amax_idx = nullptr;
   // EPI_QKV: rotary embedding + KV append fused into the epilogue
   const float2 *rope_tab = nullptr;

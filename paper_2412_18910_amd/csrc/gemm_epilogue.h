@@ -30,8 +30,8 @@ struct GemmArgs {
   int RB;               // row-blocks held by the packed buffers (decode: 1)
   int w_bytes, xp_bytes;  // dense: sizes of W and Xp (buffer-load range checks)
   float eps;
-  float *amax_val;      // EPI_STORE, LM head: per row-block, per row maximum of the outputs ...
-  int32_t *amax_idx;    // ... and the lowest column index attaining it ([NBtot][16] each)
+  float *amax_val;      // EPI_STORE, LM head: per row, per row-block maximum of the outputs ...
+  int32_t *amax_idx;    // ... and the lowest column index attaining it ([16][NBtot] each)
   // EPI_QKV: rotary embedding + KV-cache append in the epilogue
   const float2 *rope_tab;   // [slot][hd/2] (cos, sin)
   uint16_t *Kc, *Vc;        // this layer's tiled bf16 cache (layouts of kernels_attn_mfma.hip)
@@ -186,7 +186,8 @@ __device__ __forceinline__ void epi_tile(const GemmArgs &a, f32x4 s, f32x4 u, in
         const int oi = __shfl_xor(bi, o2, 64);
         if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
       }
-      if (g == 0) { a.amax_val[nb * 16 + m] = bv; a.amax_idx[nb * 16 + m] = bi; }
+      // row-major by activation row ([16][NBtot]) so that the finishing kernel reads a row's partials contiguously
+      if (g == 0) { a.amax_val[(size_t)m * a.NBtot + nb] = bv; a.amax_idx[(size_t)m * a.NBtot + nb] = bi; }
     } else if (a.ssq_out) {   // partial sum of x^2 over this row-block's 16 columns
       ssq += __shfl_xor(ssq, 16, 64);
       ssq += __shfl_xor(ssq, 32, 64);

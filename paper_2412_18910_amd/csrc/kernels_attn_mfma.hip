@@ -1,10 +1,11 @@
 // Variable-length causal attention over the bf16 KV cache on the gfx950 matrix cores.
 //
-// One workgroup = one KV head x one chunk of kMfmaAttnChunk keys fixed by absolute slot; its
-// 4 waves take kMfmaKeysPerWave keys each.  (64 keys per wave measured 7.7 us per layer at 1024
-// cached tokens of the 7B shape and 11.6 us at 2100; 32 keys per wave, which doubles the
-// workgroup count, 8.2 and 11.1 us: the kernel is bound by its chain of latencies, launch ->
-// operand fetch -> combine -> store, about 5 us, not by how many compute units pull.)  All
+// One workgroup = one KV head x one chunk of 4 * KPW keys fixed by absolute slot; its 4 waves
+// take KPW = 64 keys each.  (32 keys per wave, twice the workgroups, measured per layer at the 7B
+// shape 8.2 against 7.7 us at 1024 cached tokens and 11.1 against 11.6 us at 2100, but it lost
+// 80-120 us per verify forward at the 13B / 4096-token and 8B-GQA / 8192-token shapes: every
+// workgroup repeats the query staging and the combine.)  About 5 us of the kernel are its chain
+// of latencies, launch -> operand fetch -> combine -> store.  All
 // query rows that share the KV head (rows x group size, <= 64) are processed in tiles of 16.
 // A wave issues its whole K and V working set as 1 KB coalesced loads up front, everything
 // else hides behind it.
@@ -244,15 +245,17 @@ size_t attn_mfma_smem_bytes(int MT, int HD) {
 void attention_mfma_setup() {
   const int sm128 = (int)attn_mfma_smem_bytes(4, 128), sm64 = (int)attn_mfma_smem_bytes(4, 64);
   constexpr int KPW = kMfmaKeysPerWave;
-  (void)hipFuncSetAttribute((const void *)attn_mfma_kernel<128, KPW, false>, hipFuncAttributeMaxDynamicSharedMemorySize, sm128);
-  (void)hipFuncSetAttribute((const void *)attn_mfma_kernel<128, KPW, true>, hipFuncAttributeMaxDynamicSharedMemorySize, sm128);
-  (void)hipFuncSetAttribute((const void *)attn_mfma_kernel<64, KPW, false>, hipFuncAttributeMaxDynamicSharedMemorySize, sm64);
-  (void)hipFuncSetAttribute((const void *)attn_mfma_kernel<64, KPW, true>, hipFuncAttributeMaxDynamicSharedMemorySize, sm64);
+  const auto raise = [](const void *f, int bytes) { (void)hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, bytes); };
+  raise((const void *)attn_mfma_kernel<128, KPW, false>, sm128);
+  raise((const void *)attn_mfma_kernel<128, KPW, true>, sm128);
+  raise((const void *)attn_mfma_kernel<64, KPW, false>, sm64);
+  raise((const void *)attn_mfma_kernel<64, KPW, true>, sm64);
 }
 
 template <int HD, bool GATED>
 static void launch_attention_cfg(const float *q, int rows, int pos0, const ae_config &c, const u32x4 *Kc, const u32x4 *Vc,
-                                 int n_chunks, size_t sm, float *part, void *Xp_out, hipStream_t s, const int32_t *gate) {
+                                 size_t sm, float *part, void *Xp_out, hipStream_t s, const int32_t *gate) {
+  const int n_chunks = (pos0 + rows + kMfmaAttnChunk - 1) / kMfmaAttnChunk;
   const dim3 grid(c.n_kv_heads, n_chunks);
   const float scale_log2e = 1.4426950408889634f / sqrtf((float)HD);
   attn_mfma_kernel<HD, kMfmaKeysPerWave, GATED><<<grid, 256, sm, s>>>(q, rows, pos0, c.n_heads, c.n_kv_heads, kv_capacity(c),
@@ -263,16 +266,15 @@ static void launch_attention_cfg(const float *q, int rows, int pos0, const ae_co
 
 void launch_attention_mfma(const float *q, int rows, int pos0, const ae_config &c, const void *kv_layer, size_t v_off,
                            float *part, void *Xp_out, hipStream_t s, const int32_t *gate) {
-  const int n_chunks = (pos0 + rows + kMfmaAttnChunk - 1) / kMfmaAttnChunk;
   const int G = c.n_heads / c.n_kv_heads, R = rows * G, MT = (R + 15) / 16;
   const size_t sm = attn_mfma_smem_bytes(MT, c.head_dim);
   const u32x4 *Kc = (const u32x4 *)kv_layer, *Vc = (const u32x4 *)((const char *)kv_layer + v_off);
   if (c.head_dim == 128) {
-    if (gate) launch_attention_cfg<128, true>(q, rows, pos0, c, Kc, Vc, n_chunks, sm, part, Xp_out, s, gate);
-    else launch_attention_cfg<128, false>(q, rows, pos0, c, Kc, Vc, n_chunks, sm, part, Xp_out, s, gate);
+    if (gate) launch_attention_cfg<128, true>(q, rows, pos0, c, Kc, Vc, sm, part, Xp_out, s, gate);
+    else launch_attention_cfg<128, false>(q, rows, pos0, c, Kc, Vc, sm, part, Xp_out, s, gate);
   } else {
-    if (gate) launch_attention_cfg<64, true>(q, rows, pos0, c, Kc, Vc, n_chunks, sm, part, Xp_out, s, gate);
-    else launch_attention_cfg<64, false>(q, rows, pos0, c, Kc, Vc, n_chunks, sm, part, Xp_out, s, gate);
+    if (gate) launch_attention_cfg<64, true>(q, rows, pos0, c, Kc, Vc, sm, part, Xp_out, s, gate);
+    else launch_attention_cfg<64, false>(q, rows, pos0, c, Kc, Vc, sm, part, Xp_out, s, gate);
   }
 }
 

@@ -218,8 +218,14 @@ static void launch_shape(const GemmArgs &a, hipStream_t s) {
   } else {
     if (a.NBtot >= 1536) launch_cfg<EPI, NORM, 8, 8, 2>(a, s);
     else if (a.NBtot >= 640) launch_cfg<EPI, NORM, 4, 8, 2>(a, s);
-    else if (a.NBtot >= 384) launch_cfg<EPI, NORM, 2, 4, 8>(a, s);
-    else launch_cfg<EPI, NORM, 1, 4, 4>(a, s);   // narrow: (1,4,8) 14.1, (1,8,4) 13.0, (1,16,1) 13.3, (1,2,8) 13.0 us against 12.9
+    // 8B-GQA QKV (384 row-blocks): (2,8,4) 12.6 us against (2,4,8) 15.6, (2,8,2) 13.5, (2,16,2) 13.0, (1,4,4) 15.2
+    else if (a.NBtot >= 384) launch_cfg<EPI, NORM, 2, 8, 4>(a, s);
+    // more row-blocks than compute units (13B o / down, 320): two per workgroup and 16 waves, 21.1 us
+    // for the pair's average against 26.9 with (1,4,4), 24.1 (2,8,4), 22.2 (2,16,4), 28.7 (1,16,2)
+    else if (a.NBtot > g_num_cus) launch_cfg<EPI, NORM, 2, 16, 2>(a, s);
+    // at most one row-block per compute unit (7B o / down, 256): (1,4,8) 14.1, (1,8,4) 13.0, (1,16,1) 13.3,
+    // (1,2,8) 13.0, (2,16,2) 16.3 us against 12.7
+    else launch_cfg<EPI, NORM, 1, 4, 4>(a, s);
   }
 }
 
@@ -280,10 +286,20 @@ __global__ __launch_bounds__(256) void argmax_finish_kernel(const float *val, co
   const int row = blockIdx.x;
   float best = -INFINITY;
   int best_i = 0x7fffffff;
-  for (int p = threadIdx.x; p < NB; p += 256) {
-    const float v = val[p * 16 + row];
-    const int i = idx[p * 16 + row];
-    if (v > best || (v == best && i < best_i)) { best = v; best_i = i; }
+  const float *vr = val + (size_t)row * NB;
+  const int32_t *ir = idx + (size_t)row * NB;
+  for (int p0 = threadIdx.x; p0 < NB; p0 += 256 * 8) {   // 8 independent coalesced loads in flight
+    float v[8];
+    int i[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int p = p0 + j * 256;
+      v[j] = p < NB ? vr[p] : -INFINITY;
+      i[j] = p < NB ? ir[p] : 0x7fffffff;
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (v[j] > best || (v[j] == best && i[j] < best_i)) { best = v[j]; best_i = i[j]; }
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {

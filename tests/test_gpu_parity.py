@@ -849,11 +849,13 @@ def test_ddd_device_rule_equals_host_rule_bf16_and_decides_next_to_the_threshold
 EDGE_BF16 = Config(2, 256, 4, 2, 64, 512, 1024, dtype=BF16, k_max=15, n_ctx_max=1024, ldlp_hidden=64)
 
 
-@pytest.mark.parametrize("n_ctx", [1, 15, 16, 17, 255, 256, 257, 511, 513])
-def test_context_lengths_around_tile_and_chunk_boundaries(n_ctx):
-    """Cached lengths next to the 16/32-slot cache tiles and the 256-key attention chunks, with
-    the widest block (k_max = 15: 16 rows, group size 2) so that blocks straddle the boundaries."""
-    cfg = EDGE_BF16
+@pytest.mark.parametrize("n_ctx,cap", [(n, 1024) for n in (1, 15, 16, 17, 255, 256, 257, 511, 513)] +
+                         [(n, 2304) for n in (31, 33, 127, 128, 129, 383, 385)])
+def test_context_lengths_around_tile_and_chunk_boundaries(n_ctx, cap):
+    """Cached lengths next to the 16/32-slot cache tiles, the 64-key spans of the attention waves
+    and the 256-key attention chunks, at two cache capacities, with the widest block (k_max = 15:
+    16 rows, group size 2) so that blocks straddle the boundaries."""
+    cfg = EDGE_BF16.with_(n_ctx_max=cap)
     eng, orc, _ = make_pair(cfg, 20)
     for layer in range(cfg.n_layers + 1):
         k, v = synth.kv_fill(cfg, n_ctx, 30 + n_ctx, layer)
