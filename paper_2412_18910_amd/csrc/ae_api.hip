@@ -257,11 +257,8 @@ void draft_lm_head(ae_ctx *c, int row, int i) {
 void enqueue_ldlp(ae_ctx *c, int slot, int f_row, bool relative_to_accept) {
   const ae_config &g = c->cfg;
   hipStream_t s = c->stream;
-  launch_ldlp_gather(c->tok_emb, g.dtype, c->hist, c->F, g.d_model, g.ldlp_in_mode, slot, f_row,
-                     relative_to_accept ? c->st : nullptr, c->ldlp_u, s);
-  const int in = g.ldlp_in_mode == 0 ? 2 * g.d_model : g.d_model;
-  launch_gemm_generic(c->ldlp_in.rowmajor, g.dtype, g.ldlp_hidden, in, c->ldlp_u, in, 1, c->ldlp_b_in, c->ldlp_z,
-                      g.ldlp_hidden, 0, s);
+  launch_ldlp_in(c->ldlp_in.rowmajor, c->ldlp_b_in, c->tok_emb, g.dtype, c->hist, c->F, g.d_model, g.ldlp_in_mode,
+                 g.ldlp_hidden, slot, f_row, relative_to_accept ? c->st : nullptr, c->ldlp_z, s);
   launch_ldlp_tail(c->ldlp_z, c->ldlp_w_res, g.dtype, c->ldlp_b_res, c->ldlp_w_out, c->ldlp_b_out, g.ldlp_hidden,
                    g.ldlp_n_res, g.k_max, g.ldlp_cls, c->st, s);
 }
@@ -582,7 +579,7 @@ int ae_init(const ae_config *cfg, const ae_weights *w, void *hip_stream, ae_ctx 
       (rc = dev_alloc(c, &c->hmid, R * f)) || (rc = dev_alloc(c, &c->F, R * d)) ||
       (rc = dev_alloc(c, &c->cat, R * 2 * d)) || (rc = dev_alloc(c, &c->logits, (size_t)(g.k_max + 1) * V)) ||
       (rc = dev_alloc(c, &c->dlogits, (size_t)(g.k_max > 0 ? g.k_max : 1) * V)) ||
-      (rc = dev_alloc(c, &c->attn_part, attn_part_floats(g))) || (rc = dev_alloc(c, &c->ldlp_u, (size_t)2 * d)) ||
+      (rc = dev_alloc(c, &c->attn_part, attn_part_floats(g))) ||
       (rc = dev_alloc(c, &c->ldlp_z, (size_t)kMaxLdlpHidden)) ||
       (rc = dev_alloc(c, &c->hist, (size_t)g.n_ctx_max + 2)) || (rc = dev_alloc(c, &c->st, 1)) ||
       (rc = dev_alloc(c, &c->prob, sample_scratch_doubles(g.vocab))))

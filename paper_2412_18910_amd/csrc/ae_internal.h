@@ -99,7 +99,7 @@ struct ae_ctx {
   float *logits = nullptr;         // [k_max+1][V]
   float *dlogits = nullptr;        // [k_max][V]
   float *attn_part = nullptr;      // split-KV partials
-  float *ldlp_u = nullptr, *ldlp_z = nullptr;
+  float *ldlp_z = nullptr;         // LDLP hidden vector
   // bf16 fast path: packed activations (GEMM B operands) and RMSNorm partial sums
   void *xp_a = nullptr, *xp_f = nullptr, *xp_att = nullptr, *xp_h = nullptr, *xp_cat = nullptr;
   float *ssq_a = nullptr, *ssq_f = nullptr;
@@ -170,8 +170,10 @@ void launch_draft_logprob(const float *logits, int V, float T, DevState *st, int
 void launch_build_block(DevState *st, const int32_t *hist, int kv_len, int k, hipStream_t s);
 // k_on_device: the draft length is st->draft_len (the block is padded to `rows` rows)
 void launch_accept_greedy(DevState *st, int32_t *hist, int kv_len, int rows, bool k_on_device, hipStream_t s);
-void launch_ldlp_gather(const void *emb, int dtype, const int32_t *hist, const float *F, int d, int in_mode,
-                        int kv_len_minus1_or_neg, int f_row, const DevState *st, float *u, hipStream_t s);
+// z0 = W_in [e ; f] + b_in (Eq. 3 input layer), e and f read in place; st_nacc != nullptr: slot and
+// row relative to the acceptance result in *st_nacc
+void launch_ldlp_in(const void *W, const float *bias, const void *emb, int dtype, const int32_t *hist, const float *F, int d,
+                    int in_mode, int h, int slot, int f_row, const DevState *st_nacc, float *z0, hipStream_t s);
 void launch_ldlp_tail(const float *z0, const void *w_res, int dtype, const float *b_res, const float *w_out,
                       const float *b_out, int h, int n_res, int k_max, int cls, DevState *st, hipStream_t s);
 void launch_rope_table(float2 *tab, int n_pos, int head_dim, float base, hipStream_t s);

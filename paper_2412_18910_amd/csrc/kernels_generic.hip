@@ -289,31 +289,46 @@ void launch_accept_greedy(DevState *st, int32_t *hist, int kv_len, int rows, boo
 }
 
 // ------------------------------------------------------------------ LDLP (Eq. 3)
-// u = [e ; f] (in_mode 0) or f (in_mode 1).  When use_nacc is set the row / slot are
-// taken relative to the acceptance result that an earlier kernel left in *st.
+// Input layer z0 = W_in u + b_in with u = [e ; f] (in_mode 0) or f (in_mode 1) read in place:
+// e = embedding of the last validated token (hist[slot]), f = its feature row F[f_row].  When
+// use_nacc is set, slot and row are taken relative to the acceptance result that an earlier
+// kernel left in *st.  One wave per output, lanes stride over the input in 8-element pieces
+// (the summation order of the generic GEMM).
 template <typename T>
-__global__ void ldlp_gather_kernel(const T *emb, const int32_t *hist, const float *F, int d, int in_mode, int slot,
-                                   int f_row, int use_nacc, const DevState *st, float *u) {
+__global__ __launch_bounds__(256) void ldlp_in_kernel(const T *W, const float *bias, const T *emb, const int32_t *hist,
+                                                      const float *F, int d, int in_mode, int h, int slot, int f_row,
+                                                      int use_nacc, const DevState *st, float *z0) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int n = blockIdx.x * 4 + wave;
+  if (n >= h) return;
   const int add = use_nacc ? st->n_acc : 0;
   const float *f = F + (size_t)(f_row + add) * d;
-  if (in_mode == 0) {
-    const T *e = emb + (size_t)hist[slot + add] * d;
-    for (int i = threadIdx.x; i < d; i += blockDim.x) {
-      u[i] = ld1(e + i);
-      u[d + i] = f[i];
-    }
-  } else {
-    for (int i = threadIdx.x; i < d; i += blockDim.x) u[i] = f[i];
+  const T *e = emb + (size_t)hist[slot + add] * d;
+  const int K = in_mode == 0 ? 2 * d : d;
+  const T *wrow = W + (size_t)n * K;
+  float acc = 0.f;
+  for (int k0 = lane * 8; k0 < K; k0 += 512) {
+    float w[8], x[8];
+    ld8(wrow + k0, w);
+    if (in_mode == 0 && k0 < d) ld8(e + k0, x);
+    else ld8(f + (in_mode == 0 ? k0 - d : k0), x);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc = fmaf(x[j], w[j], acc);
   }
+  acc = wave_sum(acc);
+  if (lane == 0) z0[n] = acc + bias[n];
 }
 
-void launch_ldlp_gather(const void *emb, int dtype, const int32_t *hist, const float *F, int d, int in_mode,
-                        int slot, int f_row, const DevState *st_nacc, float *u, hipStream_t s) {
+void launch_ldlp_in(const void *W, const float *bias, const void *emb, int dtype, const int32_t *hist, const float *F, int d,
+                    int in_mode, int h, int slot, int f_row, const DevState *st_nacc, float *z0, hipStream_t s) {
   const int use = st_nacc != nullptr;
+  const dim3 grid((h + 3) / 4);
   if (dtype == AE_BF16)
-    ldlp_gather_kernel<bf16_t><<<1, 1024, 0, s>>>((const bf16_t *)emb, hist, F, d, in_mode, slot, f_row, use, st_nacc, u);
+    ldlp_in_kernel<bf16_t><<<grid, 256, 0, s>>>((const bf16_t *)W, bias, (const bf16_t *)emb, hist, F, d, in_mode, h, slot,
+                                                f_row, use, st_nacc, z0);
   else
-    ldlp_gather_kernel<float><<<1, 1024, 0, s>>>((const float *)emb, hist, F, d, in_mode, slot, f_row, use, st_nacc, u);
+    ldlp_in_kernel<float><<<grid, 256, 0, s>>>((const float *)W, bias, (const float *)emb, hist, F, d, in_mode, h, slot,
+                                               f_row, use, st_nacc, z0);
 }
 
 // z0 = W_in u + b_in comes from the GEMM; here: residual blocks z += silu(W_r z + b_r),
