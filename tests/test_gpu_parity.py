@@ -846,6 +846,46 @@ def test_ddd_device_rule_equals_host_rule_bf16_and_decides_next_to_the_threshold
     eng_d.close()
 
 
+def test_ddd_device_rule_equals_host_rule_bf16_sampling():
+    """bf16 path at temperature > 0 with the exit rule on: sampled drafts, rejection sampling on a
+    padded block (the accept kernels take the drafted length from the device) - the two modes agree
+    bit for bit, and the statistic is the log-probability of the SAMPLED tokens under softmax(l/T)."""
+    from paper_2412_18910_amd.binding import Engine
+    from .gpu_helpers import to_device
+    T = 0.7
+    cfg = SMALL_BF16.with_(temperature=T, ddd_enabled=1, ddd_threshold=-14.0)
+    w = to_device(synth.make_weights(cfg, 61))
+    ids = synth.token_ids(80, cfg.vocab, 302)
+    eng_h, eng_d = Engine(cfg, w), Engine(cfg, w)
+    eng_h.set_ddd_mode(Engine.DDD_HOST)
+    eng_d.set_ddd_mode(Engine.DDD_DEVICE)
+    eng_h.prefill(ids)
+    eng_d.prefill(ids)
+    lens = []
+    for r in range(12):
+        k = r % 3
+        ud, ua = synth.uniforms(cfg.k_max, 7000 + r), synth.uniforms(cfg.k_max + 1, 8000 + r)
+        if r % 4 == 3:      # un-padded use: the id output synchronises, then verify / accept with the real length
+            dh, dd = eng_h.draft(k, u_draft=ud), eng_d.draft(k, u_draft=ud)
+            assert np.array_equal(dh, dd)
+            lp = sum(_logp64(eng_d.draft_logits(i), dd[i], T) for i in range(len(dd)))
+            assert abs(eng_d.draft_logprob - lp) < 1e-3 * max(1.0, abs(lp) / 10)
+            eng_h.verify(n_rows=len(dh) + 1)
+            eng_d.verify(n_rows=len(dd) + 1)
+            assert eng_h.accept(ua[:len(dh) + 1]) == eng_d.accept(ua[:len(dd) + 1])
+            lens.append(len(dd))
+        else:
+            sh = eng_h.step(k_force=k, u_draft=ud, u_accept=ua)
+            sd = eng_d.step(k_force=k, u_draft=ud, u_accept=ua)
+            assert sh[:2] == sd[:2] and np.array_equal(sh[2], sd[2]), (r, sh, sd)
+            assert eng_h.draft_logprob == eng_d.draft_logprob
+            lens.append(sh[0])
+        assert eng_h.kv_len == eng_d.kv_len and eng_h.pending == eng_d.pending
+    assert min(lens) < cfg.k_max and max(l - r % 3 for r, l in enumerate(lens)) > 0, lens   # the rule both stopped and extended
+    eng_h.close()
+    eng_d.close()
+
+
 EDGE_BF16 = Config(2, 256, 4, 2, 64, 512, 1024, dtype=BF16, k_max=15, n_ctx_max=1024, ldlp_hidden=64)
 
 
