@@ -226,7 +226,7 @@ void draft_rows(ae_ctx *c, const float *feat, int feat_ld, const int32_t *next_i
 // LM head (shared with the target) on draft-head output row `row` -> dlogits[i], then the
 // head's token i: argmax (greedy) or an inverse-CDF sample driven by u_draft[i] (temperature
 // > 0); the caller's override table is applied last.
-void draft_lm_head(ae_ctx *c, int row, int i) {
+void draft_lm_head(ae_ctx *c, int row, int i, int k) {
   const ae_config &g = c->cfg;
   hipStream_t s = c->stream;
   float *dl = c->dlogits + (size_t)i * g.vocab;
@@ -235,16 +235,22 @@ void draft_lm_head(ae_ctx *c, int row, int i) {
     GemmLaunch lm;
     lm.W = &c->lm_head; lm.Xp = c->xp_cat; lm.rows = 1; lm.row0 = row; lm.epi = EPI_STORE;
     lm.Y[0] = dl; lm.ldy[0] = g.vocab; lm.seg_N[0] = g.vocab;
-    if (greedy) { lm.amax_val = c->amax_val; lm.amax_idx = c->amax_idx; }
+    DddFinish ddd;   // the DDD rule's statistic rides on the LM-head epilogue and on the kernel that fixes the token
+    if (g.ddd_enabled) {
+      ddd.val = c->amax_val; ddd.lse_sum = c->lse_sum; ddd.logits = dl; ddd.NB = g.vocab / 16; ddd.k = k;
+      ddd.inv_t = greedy ? 1.f : 1.f / g.temperature; ddd.theta = g.ddd_threshold;
+      lm.lse_sum = c->lse_sum; lm.lse_inv_t = ddd.inv_t;
+    }
+    if (greedy || g.ddd_enabled) { lm.amax_val = c->amax_val; lm.amax_idx = c->amax_idx; }
     lm.gate = c->gate;
     launch_gemm_mfma(lm, s);
     DraftCat cat;   // the picked token's embedding joins the head's output in its packed input row
     cat.emb = c->tok_emb; cat.Xp = c->xp_cat; cat.d = g.d_model; cat.row = row;
     if (greedy) {
-      launch_argmax_finish(c->amax_val, c->amax_idx, g.vocab / 16, 1, c->st, i, s, c->gate, cat);   // argmax + override
+      launch_argmax_finish(c->amax_val, c->amax_idx, g.vocab / 16, 1, c->st, i, s, c->gate, cat, ddd);   // argmax + override
     } else {
       launch_sample_draft(dl, g.vocab, g.temperature, c->st, i, c->prob, s, c->gate);
-      launch_pick_draft_packed(c->st, i, s, c->gate, cat);
+      launch_pick_draft_packed(c->st, i, s, c->gate, cat, ddd);
     }
     return;
   }
@@ -252,6 +258,7 @@ void draft_lm_head(ae_ctx *c, int row, int i) {
   if (greedy) launch_argmax(dl, 1, g.vocab, c->st->argmax, s, c->gate);
   else launch_sample_draft(dl, g.vocab, g.temperature, c->st, i, c->prob, s, c->gate);
   launch_pick_draft(c->st, i, s, c->gate);
+  if (g.ddd_enabled) launch_draft_logprob(dl, g.vocab, g.temperature, c->st, i, k, g.ddd_threshold, s, c->gate);
 }
 
 void enqueue_ldlp(ae_ctx *c, int slot, int f_row, bool relative_to_accept) {
@@ -547,7 +554,8 @@ int ae_init(const ae_config *cfg, const ae_weights *w, void *hip_stream, ae_ctx 
         (rc = dev_alloc(c, &pt, dqq * 64)) || (rc = dev_alloc(c, &ph, (size_t)g.d_ffn * 64)) ||
         (rc = dev_alloc(c, &pc, (size_t)2 * g.d_model * 64)) ||
         (rc = dev_alloc(c, &c->ssq_a, (size_t)g.d_model)) || (rc = dev_alloc(c, &c->ssq_f, (size_t)g.d_model)) ||
-        (rc = dev_alloc(c, &c->amax_val, (size_t)g.vocab)) || (rc = dev_alloc(c, &c->amax_idx, (size_t)g.vocab)))
+        (rc = dev_alloc(c, &c->amax_val, (size_t)g.vocab)) || (rc = dev_alloc(c, &c->amax_idx, (size_t)g.vocab)) ||
+        (rc = dev_alloc(c, &c->lse_sum, (size_t)g.vocab)))
       return bail(rc);
     c->xp_a = pa; c->xp_f = pf; c->xp_att = pt; c->xp_h = ph; c->xp_cat = pc;
     launch_fill_zero(pa, (size_t)g.d_model * 64, c->stream);
@@ -814,9 +822,7 @@ int ae_draft(ae_ctx *c, int k, const int32_t *override_ids, const double *u_draf
       fh = c->x;
       fh_row = 0;
     }
-    draft_lm_head(c, fh_row, i);
-    if (g.ddd_enabled)
-      launch_draft_logprob(c->dlogits + (size_t)i * g.vocab, g.vocab, g.temperature, c->st, i, k, g.ddd_threshold, s, c->gate);
+    draft_lm_head(c, fh_row, i, k);
   }
   c->gate = nullptr;
   k = i;   // tokens enqueued; with a gated tail the number drafted is st->draft_len <= k

@@ -105,6 +105,7 @@ struct ae_ctx {
   float *ssq_a = nullptr, *ssq_f = nullptr;
   float *amax_val = nullptr;       // LM-head argmax partials [16][vocab/16]
   int32_t *amax_idx = nullptr;
+  float *lse_sum = nullptr;        // LM-head softmax partials [16][vocab/16] (DDD rule)
   int Pa = 0;                      // number of valid partial-sum rows in ssq_a
   double *prob = nullptr;          // T>0 scratch: segment / row statistics of the sampling kernels
   int32_t *hist = nullptr;         // device token history by slot
@@ -232,6 +233,8 @@ struct GemmLaunch {
   float *ssq_out = nullptr;
   float *amax_val = nullptr;      // LM head: argmax partials per row and row-block [16][N/16]
   int32_t *amax_idx = nullptr;
+  float *lse_sum = nullptr;       // with amax_val: sum of exp((x - block max) * lse_inv_t) per row and row-block
+  float lse_inv_t = 1.f;
   // EPI_QKV: rotary embedding + KV append fused into the epilogue
   const float2 *rope_tab = nullptr;
   void *Kc = nullptr, *Vc = nullptr;
@@ -247,9 +250,19 @@ struct DraftCat {
   void *Xp = nullptr;
   int d = 0, row = 0;
 };
+// DDD bookkeeping folded into the kernel that fixes draft token i (bf16 path): the token's
+// log-probability under softmax(logits / T) from the LM-head epilogue's row-block statistics
+// (block maxima `val`, block sums `lse_sum`), the running sum, the drafted length and the exit
+// rule for the next token (see launch_draft_logprob).  lse_sum == nullptr: rule off.
+struct DddFinish {
+  const float *val = nullptr, *lse_sum = nullptr;
+  const float *logits = nullptr;   // the token's logit row
+  int NB = 0, k = 0;
+  float inv_t = 1.f, theta = 0.f;
+};
 void launch_argmax_finish(const float *val, const int32_t *idx, int NB, int rows, DevState *st, int pick_i, hipStream_t s,
-                          const int32_t *gate = nullptr, DraftCat cat = DraftCat());
-void launch_pick_draft_packed(DevState *st, int i, hipStream_t s, const int32_t *gate, DraftCat cat);
+                          const int32_t *gate = nullptr, DraftCat cat = DraftCat(), DddFinish ddd = DddFinish());
+void launch_pick_draft_packed(DevState *st, int i, hipStream_t s, const int32_t *gate, DraftCat cat, DddFinish ddd);
 void launch_embed_packed(const void *emb, const int32_t *ids_dev, int rows, int d, const float *gain, float *x,
                          void *Xp, float *ssq, hipStream_t s);
 void launch_pack_rows(const float *src, int ld, int rows, int K, const float *gain, void *Xp, hipStream_t s);

@@ -32,6 +32,8 @@ struct GemmArgs {
   float eps;
   float *amax_val;      // EPI_STORE, LM head: per row, per row-block maximum of the outputs ...
   int32_t *amax_idx;    // ... and the lowest column index attaining it ([16][NBtot] each)
+  float *lse_sum;       // with amax_val (nullable): per row, per row-block sum of exp((x - block max) * lse_inv_t)
+  float lse_inv_t;
   // EPI_QKV: rotary embedding + KV-cache append in the epilogue
   const float2 *rope_tab;   // [slot][hd/2] (cos, sin)
   uint16_t *Kc, *Vc;        // this layer's tiled bf16 cache (layouts of kernels_attn_mfma.hip)
@@ -188,6 +190,15 @@ __device__ __forceinline__ void epi_tile(const GemmArgs &a, f32x4 s, f32x4 u, in
       }
       // row-major by activation row ([16][NBtot]) so that the finishing kernel reads a row's partials contiguously
       if (g == 0) { a.amax_val[(size_t)m * a.NBtot + nb] = bv; a.amax_idx[(size_t)m * a.NBtot + nb] = bi; }
+      if (a.lse_sum) {   // softmax statistics of the row-block (log-probability of a draft token, DDD rule)
+        float e = 0.f;
+        if (row_ok)
+          e = (expf((o.x - bv) * a.lse_inv_t) + expf((o.y - bv) * a.lse_inv_t)) +
+              (expf((o.z - bv) * a.lse_inv_t) + expf((o.w - bv) * a.lse_inv_t));
+        e += __shfl_xor(e, 16, 64);
+        e += __shfl_xor(e, 32, 64);
+        if (g == 0) a.lse_sum[(size_t)m * a.NBtot + nb] = e;
+      }
     } else if (a.ssq_out) {   // partial sum of x^2 over this row-block's 16 columns
       ssq += __shfl_xor(ssq, 16, 64);
       ssq += __shfl_xor(ssq, 32, 64);

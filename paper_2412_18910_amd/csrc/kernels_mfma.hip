@@ -248,6 +248,7 @@ void launch_gemm_mfma(const GemmLaunch &L, hipStream_t s) {
   }
   const bool norm = L.ssq_in != nullptr;
   a.amax_val = L.amax_val; a.amax_idx = L.amax_idx;
+  a.lse_sum = L.amax_val ? L.lse_sum : nullptr; a.lse_inv_t = L.lse_inv_t;
   a.rope_tab = L.rope_tab; a.Kc = (uint16_t *)L.Kc; a.Vc = (uint16_t *)L.Vc;
   a.pos0 = L.pos0; a.n_ctx = L.n_ctx; a.hd = L.hd;
   a.gate = L.gate;
@@ -273,12 +274,42 @@ __device__ __forceinline__ void pack_embedding(const uint16_t *emb, int32_t t, i
   }
 }
 
+// AdaEAGLE-DDD bookkeeping behind draft token i = tok (Sec. 3.4, 4.2) from the LM-head epilogue's
+// row-block statistics of row 0; all 256 threads call.  Fixed-shape reductions.
+__device__ void ddd_finish(const DddFinish &d, int32_t tok, int i, DevState *st) {
+  __shared__ float red_s[4];
+  const int t = threadIdx.x;
+  float mx = -INFINITY;
+  for (int p = t; p < d.NB; p += 256) mx = fmaxf(mx, d.val[p]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+  if ((t & 63) == 0) red_s[t >> 6] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(red_s[0], red_s[1]), fmaxf(red_s[2], red_s[3]));
+  __syncthreads();
+  float se = 0.f;
+  for (int p = t; p < d.NB; p += 256) se += d.lse_sum[p] * expf((d.val[p] - mx) * d.inv_t);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) se += __shfl_xor(se, o, 64);
+  if ((t & 63) == 0) red_s[t >> 6] = se;
+  __syncthreads();
+  if (t == 0) {
+    se = (red_s[0] + red_s[1]) + (red_s[2] + red_s[3]);
+    const float lp = (d.logits[tok] - mx) * d.inv_t - logf(se);
+    const float cum = (i == 0 ? 0.f : st->cum_logp) + lp;
+    st->draft_lp[i] = lp;
+    st->cum_logp = cum;
+    st->draft_len = i + 1;
+    if (i + 1 >= d.k && !(cum >= d.theta)) st->draft_live = 0;
+  }
+}
+
 // Final argmax over the LM head's row-block partials (lowest token id wins ties), one
 // workgroup per row.  pick_i >= 0 (draft head, one row): also applies the caller's override
 // table, records draft token pick_i and, when cat.Xp is set, writes that token's embedding into
 // the draft head's packed input row for the next chained forward.
 __global__ __launch_bounds__(256) void argmax_finish_kernel(const float *val, const int32_t *idx, int NB, DevState *st,
-                                                            int pick_i, const int32_t *gate, DraftCat cat) {
+                                                            int pick_i, const int32_t *gate, DraftCat cat, DddFinish ddd) {
   __shared__ float bv[4];
   __shared__ int bi[4];
   __shared__ int32_t tok_s;
@@ -320,29 +351,32 @@ __global__ __launch_bounds__(256) void argmax_finish_kernel(const float *val, co
     }
     tok_s = t;
   }
-  if (pick_i >= 0 && cat.Xp) {
+  if (pick_i >= 0 && (cat.Xp || ddd.lse_sum)) {
     __syncthreads();
-    pack_embedding((const uint16_t *)cat.emb, tok_s, cat.d, (u32x4 *)cat.Xp, cat.row, cat.d);
+    if (cat.Xp) pack_embedding((const uint16_t *)cat.emb, tok_s, cat.d, (u32x4 *)cat.Xp, cat.row, cat.d);
+    if (ddd.lse_sum) ddd_finish(ddd, tok_s, pick_i, st);
   }
 }
 
 void launch_argmax_finish(const float *val, const int32_t *idx, int NB, int rows, DevState *st, int pick_i, hipStream_t s,
-                          const int32_t *gate, DraftCat cat) {
-  argmax_finish_kernel<<<rows, 256, 0, s>>>(val, idx, NB, st, pick_i, gate, cat);
+                          const int32_t *gate, DraftCat cat, DddFinish ddd) {
+  argmax_finish_kernel<<<rows, 256, 0, s>>>(val, idx, NB, st, pick_i, gate, cat, ddd);
 }
 
 // temperature > 0: the sampled token (st->argmax[0]) with the override table applied becomes draft
 // token i; its embedding goes into the draft head's packed input row like above
-__global__ __launch_bounds__(256) void pick_draft_packed_kernel(DevState *st, int i, const int32_t *gate, DraftCat cat) {
+__global__ __launch_bounds__(256) void pick_draft_packed_kernel(DevState *st, int i, const int32_t *gate, DraftCat cat,
+                                                                DddFinish ddd) {
   AE_GATE(gate);
   int32_t t = st->argmax[0];
   if (st->override_ids[i] >= 0) t = st->override_ids[i];
   if (threadIdx.x == 0) st->draft_ids[i] = t;
   pack_embedding((const uint16_t *)cat.emb, t, cat.d, (u32x4 *)cat.Xp, cat.row, cat.d);
+  if (ddd.lse_sum) ddd_finish(ddd, t, i, st);
 }
 
-void launch_pick_draft_packed(DevState *st, int i, hipStream_t s, const int32_t *gate, DraftCat cat) {
-  pick_draft_packed_kernel<<<1, 256, 0, s>>>(st, i, gate, cat);
+void launch_pick_draft_packed(DevState *st, int i, hipStream_t s, const int32_t *gate, DraftCat cat, DddFinish ddd) {
+  pick_draft_packed_kernel<<<1, 256, 0, s>>>(st, i, gate, cat, ddd);
 }
 
 // ------------------------------------------------------------------ packed-form producers
