@@ -94,7 +94,6 @@ struct ae_ctx {
   float *x = nullptr, *xn = nullptr, *q = nullptr, *kbuf = nullptr, *vbuf = nullptr, *att = nullptr;
   float *gate_proj = nullptr, *up = nullptr, *hmid = nullptr;
   float *F = nullptr;              // feature rows (post final norm)
-  float *fhat = nullptr;           // draft-head output rows
   float *cat = nullptr;            // [rows][2d] draft fc input
   float *logits = nullptr;         // [k_max+1][V]
   float *dlogits = nullptr;        // [k_max][V]
@@ -187,7 +186,6 @@ int kv_capacity(const ae_config &c);   // n_ctx_max rounded up to a whole attent
 void launch_rope_append(float *q, const float *k, const float *v, int rows, int pos0, const ae_config &c,
                         const float2 *rope_tab, void *kv_layer, size_t v_off, bool tiled, hipStream_t s,
                         const int32_t *gate = nullptr);
-void launch_attn_merge(const float *part, int rows, const ae_config &c, int n_chunks, float *out, hipStream_t s);
 // bf16 MFMA attention over the tiled cache layout (kernels_attn_mfma.hip)
 void attention_mfma_setup();   // once per context set-up: dynamic LDS limit of the kernels
 void launch_attention_mfma(const float *q, int rows, int pos0, const ae_config &c, const void *kv_layer, size_t v_off,

@@ -264,13 +264,6 @@ size_t attn_part_floats(const ae_config &c) {
   return (size_t)c.n_heads * max_chunks * kMaxRows * (c.head_dim + 2);
 }
 
-void launch_attn_merge(const float *part, int rows, const ae_config &c, int n_chunks, float *out, hipStream_t s) {
-  if (c.head_dim == 128)
-    attn_merge_kernel<128><<<rows * c.n_heads, 128, 0, s>>>(part, rows, c.n_heads, c.n_kv_heads, n_chunks, out, nullptr);
-  else
-    attn_merge_kernel<64><<<rows * c.n_heads, 64, 0, s>>>(part, rows, c.n_heads, c.n_kv_heads, n_chunks, out, nullptr);
-}
-
 void launch_attention(const float *q, int rows, int pos0, const ae_config &c, const void *kv_layer, size_t v_off,
                       float *part, float *out, hipStream_t s, const int32_t *gate) {
   const int n_chunks = (pos0 + rows + kAttnChunk - 1) / kAttnChunk;
