@@ -595,8 +595,7 @@ int ae_init(const ae_config *cfg, const ae_weights *w, void *hip_stream, ae_ctx 
   launch_rope_table(c->rope_tab, g.n_ctx_max, g.head_dim, g.rope_base, c->stream);
   launch_fill_zero(c->st, (sizeof(DevState) + 15) / 16 * 16, c->stream);
   launch_fill_zero(c->hist, ((size_t)(g.n_ctx_max + 2) * 4 + 15) / 16 * 16, c->stream);
-  if (hipHostMalloc((void **)&c->h_st, sizeof(DevState), hipHostMallocDefault) != hipSuccess ||
-      hipHostMalloc((void **)&c->h_ids, sizeof(DevState), hipHostMallocDefault) != hipSuccess) {
+  if (hipHostMalloc((void **)&c->h_st, sizeof(DevState), hipHostMallocDefault) != hipSuccess) {
     c->err = "hipHostMalloc failed";
     return bail(AE_ENOMEM);
   }
@@ -617,7 +616,6 @@ void ae_free(ae_ctx *c) {
   for (void *p : c->owned) hipFree(p);
   for (void *p : c->dense_owned) hipFree(p);
   if (c->h_st) hipHostFree(c->h_st);
-  if (c->h_ids) hipHostFree(c->h_ids);
   for (auto &e : c->ev)
     if (e) hipEventDestroy(e);
   for (auto &e : c->kt_ev) hipEventDestroy(e);
@@ -777,17 +775,8 @@ int ae_draft(ae_ctx *c, int k, const int32_t *override_ids, const double *u_draf
     for (int i = 0; i < n_ov; ++i)
       if (!(u_draft[i] >= 0.0 && u_draft[i] < 1.0)) return fail(c, AE_EINVAL, "ae_draft: u_draft outside [0,1)");
   hipStream_t s = c->stream;
-  // upload the override table (-1 = keep the head's own token), the chain gate and the sampling uniforms
-  DevState *up = (DevState *)c->h_ids;
-  for (int i = 0; i < kMaxRows; ++i) up->override_ids[i] = (override_ids && i < n_ov) ? override_ids[i] : -1;
-  up->draft_live = 1;
-  up->draft_len = 0;
-  HIPCHK(c, hipMemcpyAsync(c->st->override_ids, up->override_ids, sizeof(up->override_ids) + 2 * sizeof(int32_t),
-                           hipMemcpyHostToDevice, s));
-  if (sampling && n_ov > 0) {
-    for (int i = 0; i < n_ov; ++i) up->u_draft[i] = u_draft[i];
-    HIPCHK(c, hipMemcpyAsync(c->st->u_draft, up->u_draft, sizeof(double) * n_ov, hipMemcpyHostToDevice, s));
-  }
+  // override table (-1 = keep the head's own token), chain gate reset and the sampling uniforms
+  launch_set_draft_inputs(c->st, override_ids, n_ov, sampling ? u_draft : nullptr, n_ov, s);
   // catch-up over the slots validated by the last accept: true feature + following token
   draft_rows(c, c->F + (size_t)(c->nF - catch_rows) * g.d_model, g.d_model, c->hist + c->dlen + 1, catch_rows, c->dlen);
   c->dlen = n;
@@ -853,10 +842,7 @@ int ae_verify(ae_ctx *c, const int32_t *block_ids, int rows) {
   hipStream_t s = c->stream;
   if (block_ids) {
     if (!ids_ok(c, block_ids, rows)) return fail(c, AE_EINVAL, "ae_verify: token id out of range");
-    // the staging buffer may still feed an earlier asynchronous upload
-    HIPCHK(c, hipStreamSynchronize(s));
-    memcpy(c->h_ids, block_ids, sizeof(int32_t) * rows);
-    HIPCHK(c, hipMemcpyAsync(c->st->block, c->h_ids, sizeof(int32_t) * rows, hipMemcpyHostToDevice, s));
+    launch_set_block(c->st, block_ids, rows, s);
   } else {
     if (!c->have_draft || rows != c->cur_k + 1)
       return fail(c, AE_ESTATE, "ae_verify: implicit block needs a draft of rows-1 tokens");
@@ -876,12 +862,9 @@ int ae_accept(ae_ctx *c, const double *u, int *n_accepted, int32_t *bonus) {
   if (g.temperature > 0.f) {
     if (!u) return fail(c, AE_EINVAL, "ae_accept: temperature > 0 needs the uniforms u");
     if (rows > 1 && !c->have_draft) return fail(c, AE_ESTATE, "ae_accept: rejection sampling needs the draft's own logits");
-    DevState *up = (DevState *)c->h_ids;
-    for (int i = 0; i < rows; ++i) {
+    for (int i = 0; i < rows; ++i)
       if (!(u[i] >= 0.0 && u[i] < 1.0)) return fail(c, AE_EINVAL, "ae_accept: u outside [0,1)");
-      up->u_accept[i] = u[i];
-    }
-    HIPCHK(c, hipMemcpyAsync(c->st->u_accept, up->u_accept, sizeof(double) * rows, hipMemcpyHostToDevice, c->stream));
+    launch_set_u_accept(c->st, u, rows, c->stream);
     launch_accept_sample(c->logits, c->dlogits, g.vocab, rows - 1, c->k_on_device, g.temperature, c->st, c->hist, n,
                          c->prob, c->stream);
   } else {

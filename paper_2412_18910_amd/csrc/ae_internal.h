@@ -29,7 +29,7 @@ struct DevState {
   float y_next;             // LDLP scalar before rounding
   int32_t draft_ids[kMaxRows];
   int32_t override_ids[kMaxRows];
-  // Device-gated DDD chain (uploaded together with override_ids): every kernel of a draft token
+  // Device-gated DDD chain (reset together with override_ids): every kernel of a draft token
   // past the predicted length reads draft_live at entry and returns when it is 0; draft_len
   // counts the tokens drafted.
   int32_t draft_live;
@@ -41,8 +41,6 @@ struct DevState {
   float cum_logp;           // log-probability of the current draft sequence (DDD exit rule)
   float draft_lp[kMaxRows]; // per-token log-probabilities
 };
-static_assert(offsetof(DevState, draft_len) == offsetof(DevState, override_ids) + sizeof(int32_t) * (kMaxRows + 1),
-              "override_ids, draft_live, draft_len are uploaded as one range");
 static_assert(offsetof(DevState, u_draft) % 8 == 0, "doubles must stay aligned");
 
 // A kernel launched with a non-null gate pointer does nothing when *gate == 0.
@@ -110,7 +108,6 @@ struct ae_ctx {
   int32_t *hist = nullptr;         // device token history by slot
   ae::DevState *st = nullptr;      // device state
   ae::DevState *h_st = nullptr;    // pinned host mirror used for read-back / uploads
-  int32_t *h_ids = nullptr;        // pinned staging for ids
 
   // dense prompt pass (bf16 only): chunk buffers, allocated at the first long prompt
   int prefill_mode = 0;            // AE_PREFILL_AUTO / _BLOCKS / _DENSE
@@ -167,6 +164,12 @@ void launch_pick_draft(DevState *st, int i, hipStream_t s, const int32_t *gate =
 // token: st->draft_live = 0 when i + 1 >= k and the sequence log-probability is below theta.
 void launch_draft_logprob(const float *logits, int V, float T, DevState *st, int i, int k, float theta, hipStream_t s,
                           const int32_t *gate = nullptr);
+// Host arrays (override ids: -1 keeps the head's own token; uniforms; explicit block ids) are
+// passed by value inside the launch; the pointers are read before the call returns.
+void launch_set_draft_inputs(DevState *st, const int32_t *override_ids, int n_ov, const double *u_draft, int n_u,
+                             hipStream_t s);
+void launch_set_block(DevState *st, const int32_t *ids, int rows, hipStream_t s);
+void launch_set_u_accept(DevState *st, const double *u, int rows, hipStream_t s);
 void launch_build_block(DevState *st, const int32_t *hist, int kv_len, int k, hipStream_t s);
 // k_on_device: the draft length is st->draft_len (the block is padded to `rows` rows)
 void launch_accept_greedy(DevState *st, int32_t *hist, int kv_len, int rows, bool k_on_device, hipStream_t s);

@@ -264,6 +264,51 @@ void launch_draft_logprob(const float *logits, int V, float T, DevState *st, int
   draft_logprob_kernel<<<1, 1024, 0, s>>>(logits, V, T > 0.f ? 1.0f / T : 1.0f, st, i, k, theta, gate);
 }
 
+// Small host values reach the device state as kernel arguments: the launch carries them, so no
+// staging buffer has to outlive the call and no copy engine is involved.
+struct HostIds { int32_t v[kMaxRows]; };
+struct HostUniforms { double v[kMaxRows]; };
+
+__global__ void set_draft_inputs_kernel(DevState *st, HostIds ov, HostUniforms u, int n_u) {
+  const int t = threadIdx.x;
+  if (t < kMaxRows) {
+    st->override_ids[t] = ov.v[t];
+    if (t < n_u) st->u_draft[t] = u.v[t];
+  }
+  if (t == 0) {
+    st->draft_live = 1;
+    st->draft_len = 0;
+  }
+}
+void launch_set_draft_inputs(DevState *st, const int32_t *override_ids, int n_ov, const double *u_draft, int n_u,
+                             hipStream_t s) {
+  HostIds ov;
+  HostUniforms u;
+  for (int i = 0; i < kMaxRows; ++i) {
+    ov.v[i] = (override_ids && i < n_ov) ? override_ids[i] : -1;
+    u.v[i] = (u_draft && i < n_u) ? u_draft[i] : 0.0;
+  }
+  set_draft_inputs_kernel<<<1, 64, 0, s>>>(st, ov, u, u_draft ? n_u : 0);
+}
+
+__global__ void set_block_kernel(DevState *st, HostIds ids, int rows) {
+  if ((int)threadIdx.x < rows) st->block[threadIdx.x] = ids.v[threadIdx.x];
+}
+void launch_set_block(DevState *st, const int32_t *ids, int rows, hipStream_t s) {
+  HostIds h;
+  for (int i = 0; i < kMaxRows; ++i) h.v[i] = i < rows ? ids[i] : 0;
+  set_block_kernel<<<1, 64, 0, s>>>(st, h, rows);
+}
+
+__global__ void set_u_accept_kernel(DevState *st, HostUniforms u, int rows) {
+  if ((int)threadIdx.x < rows) st->u_accept[threadIdx.x] = u.v[threadIdx.x];
+}
+void launch_set_u_accept(DevState *st, const double *u, int rows, hipStream_t s) {
+  HostUniforms h;
+  for (int i = 0; i < kMaxRows; ++i) h.v[i] = i < rows ? u[i] : 0.0;
+  set_u_accept_kernel<<<1, 64, 0, s>>>(st, h, rows);
+}
+
 __global__ void build_block_kernel(DevState *st, const int32_t *hist, int kv_len, int k) {
   if (threadIdx.x == 0) st->block[0] = hist[kv_len];
   if ((int)threadIdx.x < k) st->block[1 + threadIdx.x] = st->draft_ids[threadIdx.x];
