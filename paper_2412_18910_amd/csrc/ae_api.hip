@@ -267,7 +267,7 @@ void enqueue_ldlp(ae_ctx *c, int slot, int f_row, bool relative_to_accept) {
   launch_ldlp_in(c->ldlp_in.rowmajor, c->ldlp_b_in, c->tok_emb, g.dtype, c->hist, c->F, g.d_model, g.ldlp_in_mode,
                  g.ldlp_hidden, slot, f_row, relative_to_accept ? c->st : nullptr, c->ldlp_z, s);
   launch_ldlp_tail(c->ldlp_z, c->ldlp_w_res, g.dtype, c->ldlp_b_res, c->ldlp_w_out, c->ldlp_b_out, g.ldlp_hidden,
-                   g.ldlp_n_res, g.k_max, g.ldlp_cls, c->st, s);
+                   g.ldlp_n_res, g.k_max, g.ldlp_cls, c->st, c->h_st_dev, s);
 }
 
 // after a stream synchronisation: fold the finished event pairs into the totals
@@ -282,8 +282,11 @@ void drain_kernel_timing(ae_ctx *c) {
   c->kt_used = 0;
 }
 
-int read_state(ae_ctx *c) {
-  HIPCHK(c, hipMemcpyAsync(c->h_st, c->st, sizeof(DevState), hipMemcpyDeviceToHost, c->stream));
+// Bring the host's mirror of the device state up to date and wait for it.  The mirror is pinned
+// host memory that the device writes itself; `published`: the last kernel enqueued (the LDLP
+// tail) has already done so.
+int read_state(ae_ctx *c, bool published = false) {
+  if (!published) launch_publish_state(c->st, c->h_st_dev, c->stream);
   HIPCHK(c, hipStreamSynchronize(c->stream));
   HIPCHK(c, hipGetLastError());
   if (c->kt_used) drain_kernel_timing(c);
@@ -595,9 +598,14 @@ int ae_init(const ae_config *cfg, const ae_weights *w, void *hip_stream, ae_ctx 
   launch_rope_table(c->rope_tab, g.n_ctx_max, g.head_dim, g.rope_base, c->stream);
   launch_fill_zero(c->st, (sizeof(DevState) + 15) / 16 * 16, c->stream);
   launch_fill_zero(c->hist, ((size_t)(g.n_ctx_max + 2) * 4 + 15) / 16 * 16, c->stream);
-  if (hipHostMalloc((void **)&c->h_st, sizeof(DevState), hipHostMallocDefault) != hipSuccess) {
+  if (hipHostMalloc((void **)&c->h_st, sizeof(DevState), hipHostMallocMapped) != hipSuccess) {
     c->err = "hipHostMalloc failed";
     return bail(AE_ENOMEM);
+  }
+  memset(c->h_st, 0, sizeof(DevState));
+  if (hipHostGetDevicePointer((void **)&c->h_st_dev, c->h_st, 0) != hipSuccess) {
+    c->err = "hipHostGetDevicePointer failed";
+    return bail(AE_EHIP);
   }
   for (auto &e : c->ev)
     if (hipEventCreate(&e) != hipSuccess) { c->err = "hipEventCreate failed"; return bail(AE_EHIP); }
@@ -654,7 +662,7 @@ int ae_prefill(ae_ctx *c, const int32_t *ids, int n) {
   c->kv_len = n;
   c->dlen = n - 1;
   enqueue_ldlp(c, n - 1, c->nF - 1, false);
-  int rc = read_state(c);
+  int rc = read_state(c, true);
   if (rc) return rc;
   c->pending = c->h_st->bonus;
   c->h_hist[n] = c->pending;
@@ -747,7 +755,7 @@ int ae_ldlp(ae_ctx *c, int *k_out, float *y_out) {
   if (!c->have_pending || c->nF < 1) return fail(c, AE_ESTATE, "ae_ldlp: no validated token yet (prefill first)");
   if (!c->k_next_valid) {
     enqueue_ldlp(c, c->kv_len - 1, c->nF - 1, false);
-    int rc = read_state(c);
+    int rc = read_state(c, true);
     if (rc) return rc;
     c->k_next = c->h_st->k_next; c->y_next = c->h_st->y_next; c->k_next_valid = true;
   }
@@ -873,7 +881,7 @@ int ae_accept(ae_ctx *c, const double *u, int *n_accepted, int32_t *bonus) {
   // Alg. 1 predicts the next draft length right after the verification
   const bool spec = c->have_draft;
   if (spec) enqueue_ldlp(c, n, 0, true);
-  int rc = read_state(c);
+  int rc = read_state(c, spec);
   if (rc) return rc;
   const int acc = c->h_st->n_acc;
   for (int i = 0; i <= acc; ++i) c->h_hist[n + i] = c->h_st->block[i];

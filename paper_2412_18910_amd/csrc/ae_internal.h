@@ -107,7 +107,8 @@ struct ae_ctx {
   double *prob = nullptr;          // T>0 scratch: segment / row statistics of the sampling kernels
   int32_t *hist = nullptr;         // device token history by slot
   ae::DevState *st = nullptr;      // device state
-  ae::DevState *h_st = nullptr;    // pinned host mirror used for read-back / uploads
+  ae::DevState *h_st = nullptr;    // pinned host mirror of *st, written by the device (publish_state)
+  ae::DevState *h_st_dev = nullptr;   // the device's address of that mirror
 
   // dense prompt pass (bf16 only): chunk buffers, allocated at the first long prompt
   int prefill_mode = 0;            // AE_PREFILL_AUTO / _BLOCKS / _DENSE
@@ -177,8 +178,12 @@ void launch_accept_greedy(DevState *st, int32_t *hist, int kv_len, int rows, boo
 // row relative to the acceptance result in *st_nacc
 void launch_ldlp_in(const void *W, const float *bias, const void *emb, int dtype, const int32_t *hist, const float *F, int d,
                     int in_mode, int h, int slot, int f_row, const DevState *st_nacc, float *z0, hipStream_t s);
+// also copies the whole device state to `mirror` (device-visible pinned host memory)
 void launch_ldlp_tail(const float *z0, const void *w_res, int dtype, const float *b_res, const float *w_out,
-                      const float *b_out, int h, int n_res, int k_max, int cls, DevState *st, hipStream_t s);
+                      const float *b_out, int h, int n_res, int k_max, int cls, DevState *st, DevState *mirror,
+                      hipStream_t s);
+// *mirror = *st, written by the device itself
+void launch_publish_state(const DevState *st, DevState *mirror, hipStream_t s);
 void launch_rope_table(float2 *tab, int n_pos, int head_dim, float base, hipStream_t s);
 void launch_fill_zero(void *p, size_t bytes, hipStream_t s);
 

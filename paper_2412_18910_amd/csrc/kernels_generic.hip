@@ -333,6 +333,20 @@ void launch_accept_greedy(DevState *st, int32_t *hist, int kv_len, int rows, boo
   accept_greedy_kernel<<<1, 1, 0, s>>>(st, hist, kv_len, rows, k_on_device ? 1 : 0);
 }
 
+// The host reads the device state through a mirror in pinned host memory that the device
+// writes itself (no copy engine, no blit kernel): all threads of a workgroup call this behind
+// a barrier that follows the last write to *st; the words in [skip0, skip1) are left to the caller.
+__device__ __forceinline__ void publish_state(const DevState *st, DevState *mirror, int skip0 = 0, int skip1 = 0) {
+  const uint32_t *src = reinterpret_cast<const uint32_t *>(st);
+  uint32_t *dst = reinterpret_cast<uint32_t *>(mirror);
+  for (int i = threadIdx.x; i < (int)(sizeof(DevState) / 4); i += blockDim.x)
+    if (i < skip0 || i >= skip1) dst[i] = src[i];
+}
+__global__ void publish_state_kernel(const DevState *st, DevState *mirror) { publish_state(st, mirror); }
+void launch_publish_state(const DevState *st, DevState *mirror, hipStream_t s) {
+  publish_state_kernel<<<1, 128, 0, s>>>(st, mirror);
+}
+
 // ------------------------------------------------------------------ LDLP (Eq. 3)
 // Input layer z0 = W_in u + b_in with u = [e ; f] (in_mode 0) or f (in_mode 1) read in place:
 // e = embedding of the last validated token (hist[slot]), f = its feature row F[f_row].  When
@@ -352,6 +366,8 @@ __global__ __launch_bounds__(256) void ldlp_in_kernel(const T *W, const float *b
   const int K = in_mode == 0 ? 2 * d : d;
   const T *wrow = W + (size_t)n * K;
   float acc = 0.f;
+  // unrolled so that several iterations' loads are in flight; the products still join acc in index order
+#pragma unroll 4
   for (int k0 = lane * 8; k0 < K; k0 += 512) {
     float w[8], x[8];
     ld8(wrow + k0, w);
@@ -383,7 +399,7 @@ void launch_ldlp_in(const void *W, const float *bias, const void *emb, int dtype
 template <typename T>
 __global__ __launch_bounds__(1024) void ldlp_tail_kernel(const float *z0, const T *w_res, const float *b_res,
                                                          const float *w_out, const float *b_out, int h, int n_res,
-                                                         int k_max, int cls, DevState *st) {
+                                                         int k_max, int cls, DevState *st, DevState *mirror) {
   __shared__ float z[kMaxLdlpHidden];
   __shared__ float t[kMaxLdlpHidden];
   const int i = threadIdx.x;
@@ -415,24 +431,32 @@ __global__ __launch_bounds__(1024) void ldlp_tail_kernel(const float *z0, const 
     __syncthreads();
   }
   if (i == 0) {
-    st->y_next = best_y;
-    if (cls) {
-      st->k_next = best;
-    } else {
+    int k = best;
+    if (!cls) {
       float r = rintf(best_y);  // round half to even
       if (!(r >= 0.f)) r = 0.f;
       if (r > (float)k_max) r = (float)k_max;
-      st->k_next = (int)r;
+      k = (int)r;
     }
+    st->y_next = best_y;
+    st->k_next = k;
+    mirror->y_next = best_y;
+    mirror->k_next = k;
   }
+  // the rest of the state (acceptance result, block ids, draft bookkeeping) was written by earlier kernels
+  static_assert(offsetof(DevState, y_next) == offsetof(DevState, k_next) + 4, "k_next and y_next are adjacent words");
+  publish_state(st, mirror, offsetof(DevState, k_next) / 4, offsetof(DevState, y_next) / 4 + 1);
 }
 
 void launch_ldlp_tail(const float *z0, const void *w_res, int dtype, const float *b_res, const float *w_out,
-                      const float *b_out, int h, int n_res, int k_max, int cls, DevState *st, hipStream_t s) {
+                      const float *b_out, int h, int n_res, int k_max, int cls, DevState *st, DevState *mirror,
+                      hipStream_t s) {
   if (dtype == AE_BF16)
-    ldlp_tail_kernel<bf16_t><<<1, 1024, 0, s>>>(z0, (const bf16_t *)w_res, b_res, w_out, b_out, h, n_res, k_max, cls, st);
+    ldlp_tail_kernel<bf16_t><<<1, 1024, 0, s>>>(z0, (const bf16_t *)w_res, b_res, w_out, b_out, h, n_res, k_max, cls, st,
+                                                mirror);
   else
-    ldlp_tail_kernel<float><<<1, 1024, 0, s>>>(z0, (const float *)w_res, b_res, w_out, b_out, h, n_res, k_max, cls, st);
+    ldlp_tail_kernel<float><<<1, 1024, 0, s>>>(z0, (const float *)w_res, b_res, w_out, b_out, h, n_res, k_max, cls, st,
+                                               mirror);
 }
 
 // ------------------------------------------------------------------ set-up helpers
