@@ -63,8 +63,6 @@ int dev_alloc(ae_ctx *c, T **p, size_t count) {
   return AE_OK;
 }
 
-size_t esize(const ae_config &c) { return c.dtype == AE_BF16 ? 2 : 4; }
-
 Mat make_mat(const void *p, int N, int K) {
   Mat m;
   m.rowmajor = p; m.N = N; m.K = K;

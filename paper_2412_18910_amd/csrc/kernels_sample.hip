@@ -109,7 +109,7 @@ __device__ __forceinline__ double qval(const float *trow, const float *drow, int
 __device__ int inverse_cdf_final(const double *segtot, int S, const float *trow, const float *drow, int V, int mode, double T,
                                  double mt, double st, double md, double sd, double u, double *sh, double *total_out) {
   __shared__ double thr_s, before_s, tot_s;
-  __shared__ int owner_s, lastseg_s, res_s, lastq_s;
+  __shared__ int owner_s, res_s, lastq_s;
   const int t = threadIdx.x;
   if (t == 0) {
     double tot = 0.0;
@@ -125,7 +125,7 @@ __device__ int inverse_cdf_final(const double *segtot, int S, const float *trow,
     }
     tot_s = tot; thr_s = thr;
     if (owner < 0) { owner = lastseg; before_s = -1.0; }   // threshold beyond the total
-    owner_s = owner; lastseg_s = lastseg;
+    owner_s = owner;
     res_s = 0x7fffffff; lastq_s = -1;
   }
   __syncthreads();
