@@ -1,6 +1,5 @@
 """GPU-side test helpers: engines fed the same bytes as the oracle."""
 import numpy as np
-import torch
 
 from paper_2412_18910_amd import synth
 from paper_2412_18910_amd.binding import Engine

@@ -1,5 +1,4 @@
 """Whole-forward pins: a float64 library re-expression, block == sequential, accumulator width."""
-import math
 
 import numpy as np
 import pytest

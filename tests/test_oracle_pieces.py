@@ -1,12 +1,11 @@
 """Pins for the oracle's building blocks: closed forms, special cases, library routines."""
-import ctypes as C
 import math
 
 import numpy as np
 import pytest
 import torch
 
-from .helpers import dp, f32, fp, ip
+from .helpers import dp, f32, fp
 
 
 def test_bf16_round_matches_library_conversion(orc):
