@@ -64,7 +64,7 @@ def copy_rate(dev, mib=512, reps=6):
     return 2 * (mib << 20) / dt / 1e9
 
 
-def run_loop(preset, context, K, W, T, want_kernel_timing=True):
+def run_loop(preset, context, K, W, T, want_kernel_timing=True, weights=None):
     """The timed region for one shape: W warm-up steps, then exactly K ae_step calls bracketed
     by device synchronisation; afterwards the same steps again with phase events (and per-launch
     events on the gate/up GEMM).  Returns (results dict, engine, cfg, weights)."""
@@ -78,7 +78,7 @@ def run_loop(preset, context, K, W, T, want_kernel_timing=True):
     n_formal = (2 * K + W + 2) * (PRESETS[preset].k_max + 1) + 64
     cfg = PRESETS[preset].with_(temperature=T)
     cfg = cfg.with_(n_ctx_max=context + (3 * K + W + 2) * (cfg.k_max + 1) + 128)   # T > 0 runs three passes in a row
-    w = synth.make_weights(cfg, 1, device="cuda:0")
+    w = weights if weights is not None else synth.make_weights(cfg, 1, device="cuda:0")
     eng = Engine(cfg, w)
     ctx_ids = synth.token_ids(context, cfg.vocab, 11)
     script = synth.truncated_geometric(4 * (K + W) + 8, 3.5, cfg.k_max, 5)
@@ -184,21 +184,72 @@ def run_loop(preset, context, K, W, T, want_kernel_timing=True):
     return res, eng, cfg, w, ctx_ids, (kt_us, kt_n)
 
 
-def shape_line(preset, context, K, W):
+def calibrate_temperature(preset, context, target, weights, steps=32, iters=8):
+    """Seeded bisection on the temperature T_s that both models' logits are divided by, until the
+    random-init draft head gets `target` tokens per step accepted on average over a `steps`-step
+    dry run (rejection sampling, seeded uniforms, LDLP-chosen draft lengths).  Random-init logits
+    of the two models are nearly independent, so at temperature 1 next to nothing is accepted;
+    flattening both laws raises the overlap sum(min(p, p_hat)).  Returns (T_s, [(T, mean accepted)])."""
+    from paper_2412_18910_amd import synth
+    from paper_2412_18910_amd.binding import Engine
+    from paper_2412_18910_amd.config import PRESETS
+    base = PRESETS[preset]
+    ctx_ids = synth.token_ids(context, base.vocab, 11)
+
+    def mean_accepted(T):
+        cfg = base.with_(temperature=T, n_ctx_max=context + (steps + 2) * (base.k_max + 1) + 128)
+        eng = Engine(cfg, weights)
+        eng.prefill(ctx_ids)
+        acc = 0
+        for r in range(steps):
+            _, na, _ = eng.step(u_draft=synth.uniforms(cfg.k_max, 7000 + r), u_accept=synth.uniforms(cfg.k_max + 1, 8000 + r))
+            acc += na
+        eng.close()
+        return acc / steps
+
+    lo, hi, trace = 1.0, 64.0, []
+    for _ in range(iters):
+        mid = (lo * hi) ** 0.5
+        m = mean_accepted(mid)
+        trace.append((round(mid, 3), round(m, 3)))
+        if m < target:
+            lo = mid
+        else:
+            hi = mid
+    return round((lo * hi) ** 0.5, 3), trace
+
+
+def shape_line(preset, context, K, W, calibrate=False):
     """Short greedy loop at another workload shape, plus the accept-phase time at temperature 1
     (float64 rejection-sampling kernels over the whole vocabulary)."""
     import torch
     res, eng, cfg, w, _, _ = run_loop(preset, context, K, W, 0.0, want_kernel_timing=False)
     eng.close()
-    del eng, w
+    del eng
     torch.cuda.empty_cache()
-    rt, eng, cfg, w, _, _ = run_loop(preset, context, max(K // 2, 4), 2, 1.0, want_kernel_timing=False)
+    rt, eng, cfg, w, _, _ = run_loop(preset, context, max(K // 2, 4), 2, 1.0, want_kernel_timing=False, weights=w)
     eng.close()
-    del eng, w
+    del eng
     torch.cuda.empty_cache()
     res["workload"] = f"{preset}-shaped loop, bs=1, context {context}, k_max {cfg.k_max}, scripted acceptance (mean 3.5), greedy"
     res["temperature1"] = {"accept_phase_us": rt["phase_us"]["accept"], "ms_per_step": rt["ms_per_step"],
                            "note": "natural acceptance of the random-init head (~0): times the sampling kernels, not a speed-up"}
+    if calibrate:
+        # rejection sampling with real acceptance: a temperature scale found by seeded bisection
+        ts, trace = calibrate_temperature(preset, context, 3.0, w)
+        rc, eng, cfg, w, _, _ = run_loop(preset, context, K, W, ts, want_kernel_timing=False, weights=w)
+        eng.close()
+        del eng
+        torch.cuda.empty_cache()
+        res["temperature_scaled"] = {
+            "T_s": ts, "tokens_per_s": rc["tokens_per_s"], "ms_per_step": rc["ms_per_step"], "phase_us": rc["phase_us"],
+            "counters": rc["counters"], "ar_tokens_per_s": rc["ar_tokens_per_s"], "speedup_vs_ar": rc["speedup_vs_ar"],
+            "calibration": trace,
+            "note": "lossless rejection sampling (inverse CDF, seeded uniforms) at the temperature scale T_s that a "
+                    "32-step seeded dry run bisected to a mean of 3 accepted draft tokens per step; natural acceptance "
+                    "of the random-init draft head, LDLP-chosen draft lengths"}
+    del w
+    torch.cuda.empty_cache()
     return res
 
 
@@ -216,6 +267,9 @@ def main():
     ap.add_argument("--temperature", type=float, default=0.0,
                     help="> 0: rejection sampling with seeded uniforms and the natural acceptance of the random-init "
                          "draft head instead of the greedy loop under scripted acceptance")
+    ap.add_argument("--calibrate-temperature", type=float, default=0.0, metavar="MEAN_ACCEPTED",
+                    help="> 0: find by seeded bisection the temperature at which the random-init draft head gets this many "
+                         "tokens per step accepted, and run the loop there (overrides --temperature)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run 4 plain device copies of 512 MiB (counter calibration under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -242,7 +296,14 @@ def main():
         us = probe_read_stream(mb << 20)
         read_stream[f"{mb}MiB"] = {"us_per_launch": round(us, 2), "GBps": round((mb << 20) / us / 1e3, 1)}
 
-    res, eng, cfg, w, ctx_ids, (kt_us, kt_n) = run_loop(args.preset, args.context, K, W, T)
+    calibration = None
+    weights = None
+    if args.calibrate_temperature > 0:
+        from paper_2412_18910_amd.config import PRESETS
+        weights = synth.make_weights(PRESETS[args.preset], 1, device=dev)
+        T, calibration = calibrate_temperature(args.preset, args.context, args.calibrate_temperature, weights)
+    res, eng, cfg, w, ctx_ids, (kt_us, kt_n) = run_loop(args.preset, args.context, K, W, T, weights=weights)
+    del weights
     gate_up_bytes = 2 * 2 * cfg.d_ffn * cfg.d_model
     kern_us = kt_us / max(kt_n, 1)
     achieved = gate_up_bytes / (kern_us * 1e-6) / 1e9 if kt_n else 0.0
@@ -324,6 +385,8 @@ def main():
                      "traffic_source": "profiles/adaeagle_step_7b_bf16.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)"},
         "paper_context": "paper: 66.35 tok/s AdaEAGLE vs 39.36 AR (1.62x) on A800 fp32, Vicuna-7B, MT-Bench",
     }
+    if calibration is not None:
+        out["temperature_calibration"] = {"target_mean_accepted": args.calibrate_temperature, "T_s": T, "trace": calibration}
 
     if args.calibrate_copy:
         src = torch.empty(512 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
@@ -347,7 +410,8 @@ def main():
         shapes = {}
         for name, preset, context in (("13b_ctx4096", "13b", 4096), ("8b_gqa_ctx8192", "8b-gqa", 8192)):
             try:
-                shapes[name] = shape_line(preset, context, 16, 3)
+                # the 8B-GQA workload is the one defined with a temperature scale that gives ~3 accepted tokens
+                shapes[name] = shape_line(preset, context, 16, 3, calibrate=preset == "8b-gqa")
             except Exception as e:
                 shapes[name] = {"error": str(e)[:200]}
         out["shapes"] = shapes
