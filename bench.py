@@ -196,15 +196,16 @@ def calibrate_temperature(preset, context, target, weights, steps=32, iters=8):
     base = PRESETS[preset]
     ctx_ids = synth.token_ids(context, base.vocab, 11)
 
+    cfg = base.with_(temperature=1.0, n_ctx_max=context + (steps + 2) * (base.k_max + 1) + 128)
+    eng = Engine(cfg, weights)
+
     def mean_accepted(T):
-        cfg = base.with_(temperature=T, n_ctx_max=context + (steps + 2) * (base.k_max + 1) + 128)
-        eng = Engine(cfg, weights)
+        eng.set_temperature(T)
         eng.prefill(ctx_ids)
         acc = 0
         for r in range(steps):
             _, na, _ = eng.step(u_draft=synth.uniforms(cfg.k_max, 7000 + r), u_accept=synth.uniforms(cfg.k_max + 1, 8000 + r))
             acc += na
-        eng.close()
         return acc / steps
 
     lo, hi, trace = 1.0, 64.0, []
@@ -216,6 +217,7 @@ def calibrate_temperature(preset, context, target, weights, steps=32, iters=8):
             lo = mid
         else:
             hi = mid
+    eng.close()
     return round((lo * hi) ** 0.5, 3), trace
 
 

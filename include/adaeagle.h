@@ -183,6 +183,13 @@ int ae_draft(ae_ctx *ctx, int k, const int32_t *override_ids, const double *u_dr
 enum { AE_DDD_HOST = 0, AE_DDD_DEVICE = 1 };
 int ae_set_ddd_mode(ae_ctx *ctx, int mode);
 
+/* Temperature of the next steps (Sec. 2.1: 0 = greedy longest-prefix match, > 0 = rejection
+ * sampling with softmax(logits / T) for both models).  Replaces cfg.temperature; nothing is
+ * re-allocated and the caches stay valid.  AE_ESTATE between ae_draft and ae_accept (a draft
+ * sampled at one temperature must be judged at the same one), AE_EINVAL for a negative or
+ * non-finite value, AE_EUNSUPPORTED for T > 0 with a vocabulary above 1048576 tokens. */
+int ae_set_temperature(ae_ctx *ctx, float temperature);
+
 /* Eq. 1, forward part: target forward of an n_rows block at slots kv_len.. with causal
  * attention over the cache; row i's logits judge block token i+1.  block_ids (host)
  * NULL => the block is [pending, the k draft tokens] and n_rows must be k+1. */

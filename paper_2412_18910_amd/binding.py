@@ -22,7 +22,7 @@ EXPORTS = ("ae_init", "ae_free", "ae_last_error", "ae_prefill", "ae_kv_import", 
            "ae_draft", "ae_verify", "ae_accept", "ae_step", "ae_kv_len", "ae_pending", "ae_get_logits",
            "ae_get_feature", "ae_get_draft_logits", "ae_get_kv_row", "ae_set_profiling", "ae_get_phase_times",
            "ae_set_kernel_timing", "ae_get_kernel_timing", "ae_last_draft_len", "ae_get_draft_logprob", "ae_set_prefill_mode", "ae_version",
-           "ae_kv_import_static", "ae_ldlp_loss", "ae_set_ddd_mode", "ae_probe_read_stream")
+           "ae_kv_import_static", "ae_ldlp_loss", "ae_set_ddd_mode", "ae_set_temperature", "ae_probe_read_stream")
 
 
 class AeConfig(C.Structure):
@@ -104,6 +104,7 @@ def load_library(path=LIB_PATH):
         "ae_set_kernel_timing": (I, [P, I]),
         "ae_set_prefill_mode": (I, [P, I, I]),
         "ae_set_ddd_mode": (I, [P, I]),
+        "ae_set_temperature": (I, [P, C.c_float]),
         "ae_get_kernel_timing": (I, [P, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
         "ae_version": (C.c_char_p, []),
         "ae_probe_read_stream": (I, [P, C.c_size_t, I, I, f64p]),
@@ -294,6 +295,10 @@ class Engine:
 
     def set_ddd_mode(self, mode):
         self._chk(self.lib.ae_set_ddd_mode(self.h, int(mode)), "ae_set_ddd_mode")
+
+    def set_temperature(self, temperature):
+        self._chk(self.lib.ae_set_temperature(self.h, float(temperature)), "ae_set_temperature")
+        self.cfg = self.cfg.with_(temperature=float(temperature))
 
     def set_kernel_timing(self, on=True):
         self._chk(self.lib.ae_set_kernel_timing(self.h, int(on)), "ae_set_kernel_timing")

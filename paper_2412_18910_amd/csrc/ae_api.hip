@@ -966,6 +966,16 @@ int ae_set_ddd_mode(ae_ctx *c, int mode) {
   return AE_OK;
 }
 
+int ae_set_temperature(ae_ctx *c, float temperature) {
+  if (!c) return AE_EINVAL;
+  if (!(temperature >= 0.f) || temperature > 3.0e38f) return fail(c, AE_EINVAL, "ae_set_temperature: negative or non-finite");
+  if (temperature > 0.f && c->cfg.vocab > 1024 * 1024)
+    return fail(c, AE_EUNSUPPORTED, "temperature > 0 supports vocabularies of up to 1048576 tokens");
+  if (c->have_draft || c->have_verify) return fail(c, AE_ESTATE, "ae_set_temperature: a step is in flight (accept first)");
+  c->cfg.temperature = temperature;
+  return AE_OK;
+}
+
 int ae_kv_len(const ae_ctx *c) { return c ? c->kv_len : AE_EINVAL; }
 int ae_last_draft_len(const ae_ctx *c) { return c ? c->cur_k_last : AE_EINVAL; }
 

@@ -495,6 +495,52 @@ def test_tiny_fp32_sampling_steps_match_oracle():
     eng.close()
 
 
+def test_set_temperature_equals_an_engine_built_at_that_temperature():
+    """The temperature is a per-step parameter: an engine switched from greedy to T = 0.8 and on
+    to T = 5 produces, step for step, what the oracle built at that temperature produces."""
+    base = TINY
+    w = synth.make_weights(base, 8)
+    from paper_2412_18910_amd.binding import Engine
+    from .gpu_helpers import to_device
+    from .helpers import make_oracle
+    eng = Engine(base.with_(temperature=0.0), to_device(w))
+    ids = synth.token_ids(40, base.vocab, 83)
+    with pytest.raises(AdaEagleError) as e:
+        eng.set_temperature(-1.0)
+    assert e.value.code == AE_EINVAL
+    with pytest.raises(AdaEagleError) as e:
+        eng.set_temperature(float("nan"))
+    assert e.value.code == AE_EINVAL
+    for T in (0.8, 5.0):
+        orc, _ = make_oracle(base.with_(temperature=T), 8, weights=w)
+        orc.prefill(ids)
+        eng.set_temperature(T)
+        eng.prefill(ids)
+        for r in range(8):
+            k = 1 + (3 * r) % base.k_max
+            ud, ua = synth.uniforms(base.k_max, 500 + r), synth.uniforms(base.k_max + 1, 600 + r)
+            ko, nao, to = orc.step(k_force=k, u_draft=ud, u_accept=ua)
+            kg, nag, tg = eng.step(k_force=k, u_draft=ud, u_accept=ua)
+            assert (ko, nao) == (kg, nag) and np.array_equal(to, tg), (T, r)
+        assert eng.kv_len == orc.kv_len
+    # a draft sampled at one temperature must be judged at the same one
+    eng.draft(2, u_draft=[0.3, 0.6])
+    with pytest.raises(AdaEagleError) as e:
+        eng.set_temperature(1.0)
+    assert e.value.code == AE_ESTATE
+    eng.verify(n_rows=3)
+    eng.accept([0.1, 0.2, 0.3])
+    eng.set_temperature(0.0)      # back to greedy: no uniforms needed
+    orc0, _ = make_oracle(base, 8, weights=w)
+    orc0.prefill(ids)
+    eng.prefill(ids)
+    for r in range(4):
+        ko, nao, to = orc0.step(k_force=3)
+        kg, nag, tg = eng.step(k_force=3)
+        assert (ko, nao) == (kg, nag) and np.array_equal(to, tg), r
+    eng.close()
+
+
 def _sampling_cfgs():
     from paper_2412_18910_amd.config import LLAMA_8B_GQA
     return [(SMALL_BF16.with_(temperature=1.0), 16, 0),
