@@ -381,8 +381,9 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "gemm_mfma_kernel<EPI_SWIGLU, norm> (fused RMSNorm + gate/up + SwiGLU)",
                      "achieved": round(achieved, 1), "peak": 8000.0, "unit": "GB/s", "frac": round(achieved / 8000.0, 4),
                      "bytes_per_launch": gate_up_bytes, "avg_launch_us": round(kern_us, 2), "launches": kt_n,
-                     "timing": "HIP event pair around every launch on the launch stream (reads 2-3 us more than the "
-                               "kernel duration in a rocprofv3 trace: the pair also times the marker packets)",
+                     "timing": "HIP event pair (events without a system-scope fence) around every launch on the launch "
+                               "stream, in a pass of its own; reads ~0.5 us more than the kernel duration in a rocprofv3 "
+                               "trace: the pair also times its own marker packet",
                      "traffic": profiled_traffic() if args.preset == "7b" else None,
                      "traffic_source": "profiles/adaeagle_step_7b_bf16.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs)"},
         "paper_context": "paper: 66.35 tok/s AdaEAGLE vs 39.36 AR (1.62x) on A800 fp32, Vicuna-7B, MT-Bench",

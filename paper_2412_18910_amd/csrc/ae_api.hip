@@ -606,7 +606,7 @@ int ae_init(const ae_config *cfg, const ae_weights *w, void *hip_stream, ae_ctx 
     return bail(AE_EHIP);
   }
   for (auto &e : c->ev)
-    if (hipEventCreate(&e) != hipSuccess) { c->err = "hipEventCreate failed"; return bail(AE_EHIP); }
+    if (hipEventCreateWithFlags(&e, hipEventDisableSystemFence) != hipSuccess) { c->err = "hipEventCreate failed"; return bail(AE_EHIP); }
   c->h_hist.assign((size_t)g.n_ctx_max + 2, 0);
   c->h_block.assign(kMaxRows, 0);
   hipError_t e = hipStreamSynchronize(c->stream);
@@ -1030,7 +1030,7 @@ int ae_set_kernel_timing(ae_ctx *c, int enabled) {
     const int pairs = (c->cfg.n_layers + c->cfg.k_max + 2) * 2;
     for (int i = 0; i < 2 * pairs; ++i) {
       hipEvent_t e;
-      HIPCHK(c, hipEventCreate(&e));
+      HIPCHK(c, hipEventCreateWithFlags(&e, hipEventDisableSystemFence));
       c->kt_ev.push_back(e);
     }
   }
